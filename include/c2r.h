@@ -1,0 +1,202 @@
+/*
+ * c2r.h - C ABI of the MI355X (gfx950) hot path of a collaboration-constrained
+ * routing (C2R) Mixture-of-Experts layer, after arXiv 2504.01337.
+ *
+ * Notation follows the paper where it has one: x is a token's hidden state,
+ * W_g the router weight (Eq. 1), N (here E) the number of experts, K the
+ * experts per token, C the expert collaboration matrix (Eq. 2), T (here Tc)
+ * the length of the collaborator list Top-T(E_i) (Eq. 4).
+ *
+ * Conventions shared by every call
+ *  - Every pointer is a DEVICE pointer owned by the caller unless it says
+ *    "host".  The library never allocates, frees or keeps a pointer.
+ *  - Row-major everywhere.  Indices are int32; token counts are int64.
+ *  - `stream` is a hipStream_t passed as void*.  All work is enqueued on it and
+ *    the call returns without synchronising; stages enqueued on one stream run
+ *    in order, so a layer needs no host synchronisation between stages.
+ *  - Scratch memory comes from the caller: ask c2r_workspace_bytes() for the
+ *    stage and pass at least that many bytes, 256-byte aligned.
+ *  - Return value: C2R_OK or a negative c2r_status.  Arguments are checked on
+ *    the host before anything is launched; on error nothing was enqueued.
+ *    Expert indices and group offsets that live in device memory are range
+ *    checked inside the kernels (out-of-range experts are skipped, offsets are
+ *    clamped to the stated capacity).  inv_perm entries are trusted to be < the
+ *    number of rows of y_perm, as c2r_permute writes them.
+ *  - Implemented limits: E <= 64, K <= E, T*K < 2^31, and row sizes (d, F) that
+ *    are multiples of 8 elements.  Outside them: C2R_ERR_UNSUPPORTED.
+ */
+#ifndef C2R_H
+#define C2R_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { C2R_F32 = 0, C2R_BF16 = 1 } c2r_dtype;
+
+typedef enum {
+    C2R_OK = 0,
+    C2R_ERR_INVALID_ARG = -1, /* null pointer, K < 1, K > E, Tc < K-1, misaligned pointer ... */
+    C2R_ERR_UNSUPPORTED = -2, /* outside the implemented limits listed above */
+    C2R_ERR_WORKSPACE = -3,   /* workspace missing or smaller than c2r_workspace_bytes() */
+    C2R_ERR_LAUNCH = -4       /* the HIP runtime refused a launch (hipGetLastError kept) */
+} c2r_status;
+
+typedef enum {
+    C2R_STAGE_COACTIVATION = 0,
+    C2R_STAGE_ROUTE = 1,
+    C2R_STAGE_PERMUTE = 2,
+    C2R_STAGE_EXPERT_FFN = 3
+} c2r_stage;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int c2r_version(void);
+
+/*
+ * Length of the k-chunks of the router's summation order, a fixed constant of
+ * the ABI (256).  c2r_route computes every logit of Eq. 1 in fp32 as follows:
+ * k = 0..d-1 is cut into consecutive chunks of this length; inside a chunk one
+ * fused multiply-add per element, acc = fma(x[t,k], W_g[k,e], acc), ascending k,
+ * starting from +0; the chunk results are added left to right; the bias, if
+ * any, is added last.  An implementation of this order on another machine
+ * reproduces the logits, hence the selections, bit for bit.
+ */
+int c2r_route_chunk(void);
+
+/*
+ * Bytes of caller-provided scratch a stage needs for the given sizes (0 when it
+ * needs none).  T tokens, d model width, E experts, K experts per token, F
+ * expert intermediate width (only for C2R_STAGE_EXPERT_FFN), dt the activation
+ * type.  Host call, no GPU work.
+ */
+size_t c2r_workspace_bytes(int stage, int64_t T, int d, int E, int K, int F, c2r_dtype dt);
+
+/*
+ * Expert collaboration matrix, Eq. 2 (Sec. 3.2): for every token t and every
+ * ordered pair (i, j) of its selected experts, i = j included,
+ *     C[i, j] += 1.
+ * topk_idx : int32[T, K]  selected experts per token (entries outside [0, E)
+ *            are ignored, so a token padded with -1 counts for fewer experts)
+ * C        : int32[E, E]  in/out.  ACCUMULATES, so a corpus can be profiled
+ *            batch by batch; the caller zeroes it before the first batch.
+ * Result is exact and independent of scheduling (integer adds).
+ */
+int c2r_build_coactivation(const int32_t *topk_idx, int64_t T, int K, int E, int32_t *C,
+                           void *stream);
+
+/*
+ * Collaborator lists, Eq. 4 (Sec. 3.3, step 1): for every expert i the
+ * n = min(Tc, E-1) other experts j != i with the largest C[i, j], in
+ * descending order of count, equal counts to the lower index.  The expert
+ * itself is never in its own list (with Tc >= E-1 the constraint vanishes, as
+ * Fig. 3's caption notes for N = 8, T = 7).
+ * C           : int32[E, E]
+ * collab_idx  : int32[E, n]  out
+ * collab_mask : uint64[E] out or NULL; bit j of word i set iff j is in i's list
+ */
+int c2r_collaborators(const int32_t *C, int E, int Tc, int32_t *collab_idx, uint64_t *collab_mask,
+                      void *stream);
+
+/*
+ * Router of Eq. 1 followed by the C2R selection of Sec. 3.3 (step 2).
+ *   logits l[t, e] = sum_k x[t, k] W_g[k, e] (+ bias[e]), fp32, in the order
+ *   stated at c2r_route_chunk().
+ *   slot 0      = arg max_e l[t, e] over ALL experts (ties: lower index);
+ *   slots 1..K-1 = the K-1 largest logits among the collaborator list of the
+ *                 slot-0 expert, descending (ties: lower index);
+ *   gates[t, s] = softmax over the K kept logits (they sum to 1).
+ * collab_idx == NULL selects the conventional top-K of Eq. 1 (used to profile
+ * the pre-trained router, Sec. 3.2).
+ * x          : [T, d] of x_dt (fp32 or bf16)
+ * Wg         : fp32[d, E]   (the layout of "x . W_g")
+ * bias       : fp32[E] or NULL (per-expert logit offset; not in the paper,
+ *              used by synthetic load-skewed workloads)
+ * collab_idx : int32[E, Tc] or NULL; entries outside [0, E) or equal to the
+ *              row's own expert are ignored
+ * topk_idx   : int32[T, K] out; a slot the list cannot fill gets -1 and gate 0
+ * gates      : fp32[T, K] out
+ * logits_out : fp32[T, E] out or NULL
+ * ws         : c2r_workspace_bytes(C2R_STAGE_ROUTE, T, d, E, K, 0, x_dt)
+ * Errors: Tc < K-1 with a list given, K > E -> C2R_ERR_INVALID_ARG.
+ */
+int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const float *bias, int64_t T, int d,
+              int E, int K, const int32_t *collab_idx, int Tc, int32_t *topk_idx, float *gates,
+              float *logits_out, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The selection and gates of c2r_route applied to logits that already exist
+ * (profiling a stored logit stream, Sec. 3.2).  logits: fp32[T, E].  No scratch.
+ */
+int c2r_route_from_logits(const float *logits, int64_t T, int E, int K, const int32_t *collab_idx,
+                          int Tc, int32_t *topk_idx, float *gates, void *stream);
+
+/*
+ * Token dispatch on one device (the step the paper inherits from dropless MoE
+ * frameworks, Sec. 2 / Sec. 3.1): a stable sort of the assignments
+ * a = t*K + s by local expert slot, and the gather of their rows.
+ * local_slot : int32[E] or NULL.  local_slot[e] = position of expert e among
+ *              this device's E_local experts, or -1 if it lives elsewhere;
+ *              NULL means all E experts are local (then E_local must equal E).
+ * counts     : int32[E_local] out   rows per local expert
+ * offsets    : int32[E_local+1] out exclusive prefix sum of counts
+ * perm       : int32[T*K] out; perm[p] = a for sorted position p < offsets[E_local];
+ *              inside an expert's range a is ascending; the rest is untouched
+ * inv_perm   : int32[T*K] out; inv_perm[a] = p, or -1 if a's expert is not local
+ * x_perm     : [T*K, d] of dt out, row p = x[perm[p] / K]; may be NULL to get
+ *              the index arrays only
+ * ws         : c2r_workspace_bytes(C2R_STAGE_PERMUTE, T, d, E, K, 0, dt)
+ */
+int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T, int d, int E,
+                int K, const int32_t *local_slot, int E_local, int32_t *counts, int32_t *offsets,
+                int32_t *perm, int32_t *inv_perm, void *x_perm, void *ws, size_t ws_bytes,
+                void *stream);
+
+/*
+ * Grouped expert FFN (Sec. 3.1: "each token is fed to its selected experts"):
+ * for each local expert e and each row r in [offsets[e], offsets[e+1]):
+ *     y_perm[r] = W_down,e ( silu(W_gate,e x_perm[r]) * (W_up,e x_perm[r]) )
+ * with silu(z) = z / (1 + exp(-z)), no biases, un-weighted by the gate.
+ * bf16: products accumulate in fp32; the hidden activation is rounded to bf16
+ * once, y_perm once.  fp32: fp32 throughout.
+ * offsets : int32[E_local+1] in DEVICE memory (as written by c2r_permute)
+ * A_cap   : rows allocated in x_perm / y_perm (>= offsets[E_local], e.g. T*K)
+ * w_gate, w_up : [E_local, F, d] of dt;  w_down : [E_local, d, F] of dt
+ * y_perm  : [A_cap, d] of dt out; rows beyond offsets[E_local] are untouched
+ * ws      : c2r_workspace_bytes(C2R_STAGE_EXPERT_FFN, A_cap, d, E_local, 1, F, dt)
+ * A shared always-on expert is this call with E_local = 1, offsets = {0, T}
+ * and x itself as x_perm.
+ */
+int c2r_expert_ffn(const void *x_perm, c2r_dtype dt, const int32_t *offsets, int E_local,
+                   int64_t A_cap, int d, int F, const void *w_gate, const void *w_up,
+                   const void *w_down, void *y_perm, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The two passes of c2r_expert_ffn as calls of their own (same arguments and
+ * limits), for callers that time them or put other work between them:
+ *   gate_up : h[r, f]      = silu(W_gate,e[f,:] . x_perm[r]) * (W_up,e[f,:] . x_perm[r])
+ *   down    : y_perm[r, j] = W_down,e[j,:] . h[r]
+ * h : [A_cap, F] of dt, caller-owned (what c2r_expert_ffn keeps in its workspace).
+ */
+int c2r_expert_ffn_gate_up(const void *x_perm, c2r_dtype dt, const int32_t *offsets, int E_local,
+                           int64_t A_cap, int d, int F, const void *w_gate, const void *w_up,
+                           void *h, void *stream);
+int c2r_expert_ffn_down(const void *h, c2r_dtype dt, const int32_t *offsets, int E_local,
+                        int64_t A_cap, int d, int F, const void *w_down, void *y_perm, void *stream);
+
+/*
+ * Un-permute and gate-weighted sum (Sec. 3.1, last sentence):
+ *     y[t] = sum_{s<K, inv_perm[t*K+s] >= 0} gates[t,s] * y_perm[inv_perm[t*K+s]]  (+ y_shared[t])
+ * summed in fp32 in slot order and rounded once to dt.
+ * y_shared : [T, d] of dt or NULL (output of an always-on shared expert, weight 1)
+ * y        : [T, d] of dt out
+ */
+int c2r_combine(const void *y_perm, c2r_dtype dt, const float *gates, const int32_t *inv_perm,
+                int64_t T, int d, int K, const void *y_shared, void *y, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* C2R_H */

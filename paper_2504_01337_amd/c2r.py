@@ -1,0 +1,266 @@
+"""Thin ctypes binding of the C2R HIP library (include/c2r.h).
+
+Argument marshalling only: torch provides device memory and the current stream;
+every step of the path runs in the library's kernels.  There is no CPU or
+PyTorch fallback: if libc2r_hip.so is missing, importing the functions raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libc2r_hip.so")
+
+F32, BF16 = 0, 1
+STAGE_COACTIVATION, STAGE_ROUTE, STAGE_PERMUTE, STAGE_EXPERT_FFN = 0, 1, 2, 3
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
+_ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_WORKSPACE",
+             -4: "C2R_ERR_LAUNCH"}
+
+EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
+           "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
+           "c2r_expert_ffn_gate_up", "c2r_expert_ffn_down", "c2r_combine"]
+
+
+class C2RError(RuntimeError):
+    def __init__(self, fn, code):
+        super().__init__(f"{fn} failed: {_ERRNAMES.get(code, code)}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Load the HIP library; raise loudly if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: build it with `python -m paper_2504_01337_amd.build` "
+                              "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+        L.c2r_version.restype = i32
+        L.c2r_route_chunk.restype = i32
+        L.c2r_workspace_bytes.restype = sz
+        L.c2r_workspace_bytes.argtypes = [i32, i64, i32, i32, i32, i32, i32]
+        L.c2r_build_coactivation.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.c2r_collaborators.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.c2r_route.argtypes = [vp, i32, vp, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]
+        L.c2r_route_from_logits.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp]
+        L.c2r_permute.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.c2r_expert_ffn.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.c2r_expert_ffn_gate_up.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
+        L.c2r_expert_ffn_down.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp]
+        L.c2r_combine.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp]
+        for name in EXPORTS[3:]:
+            getattr(L, name).restype = i32
+        _lib = L
+    return _lib
+
+
+def _dt(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(fn, rc):
+    if rc != OK:
+        raise C2RError(fn, rc)
+
+
+def _ws(nbytes: int, device, ws: Optional[torch.Tensor]):
+    if ws is not None:
+        return ws
+    return torch.empty(max(int(nbytes), 256), dtype=torch.uint8, device=device)
+
+
+def version() -> int:
+    return lib().c2r_version()
+
+
+def route_chunk() -> int:
+    return lib().c2r_route_chunk()
+
+
+def workspace_bytes(stage, T, d, E, K, F, dt) -> int:
+    return int(lib().c2r_workspace_bytes(stage, T, d, E, K, F, dt))
+
+
+def build_coactivation(topk_idx: torch.Tensor, E: int, Cm: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Eq. 2.  Accumulates into Cm (int32[E,E]); a zeroed matrix is made if None."""
+    T, K = topk_idx.shape
+    if Cm is None:
+        Cm = torch.zeros((E, E), dtype=torch.int32, device=topk_idx.device)
+    _check("c2r_build_coactivation",
+           lib().c2r_build_coactivation(_ptr(topk_idx), T, K, E, _ptr(Cm), _stream()))
+    return Cm
+
+
+def collaborators(Cm: torch.Tensor, Tc: int):
+    """Eq. 4.  Returns (collab_idx int32[E, min(Tc,E-1)], collab_mask int64[E])."""
+    E = Cm.shape[0]
+    n = min(Tc, E - 1)
+    idx = torch.empty((E, n), dtype=torch.int32, device=Cm.device)
+    mask = torch.empty((E,), dtype=torch.int64, device=Cm.device)
+    _check("c2r_collaborators", lib().c2r_collaborators(_ptr(Cm), E, Tc, _ptr(idx), _ptr(mask), _stream()))
+    return idx, mask
+
+
+def route(x, Wg, bias, K, collab_idx=None, want_logits=False, ws=None, out=None):
+    """Eq. 1 + Sec. 3.3 selection.  Returns (topk_idx, gates, logits or None)."""
+    T, d = x.shape
+    E = Wg.shape[1]
+    assert Wg.shape[0] == d and Wg.dtype == torch.float32
+    dev = x.device
+    if out is None:
+        idx = torch.empty((T, K), dtype=torch.int32, device=dev)
+        gates = torch.empty((T, K), dtype=torch.float32, device=dev)
+    else:
+        idx, gates = out
+    logits = torch.empty((T, E), dtype=torch.float32, device=dev) if want_logits else None
+    Tc = 0 if collab_idx is None else collab_idx.shape[1]
+    ws = _ws(workspace_bytes(STAGE_ROUTE, T, d, E, K, 0, _dt(x)), dev, ws)
+    _check("c2r_route", lib().c2r_route(_ptr(x), _dt(x), _ptr(Wg), _ptr(bias), T, d, E, K, _ptr(collab_idx), Tc,
+                                        _ptr(idx), _ptr(gates), _ptr(logits), _ptr(ws), ws.numel(), _stream()))
+    return idx, gates, logits
+
+
+def route_from_logits(logits, K, collab_idx=None):
+    T, E = logits.shape
+    idx = torch.empty((T, K), dtype=torch.int32, device=logits.device)
+    gates = torch.empty((T, K), dtype=torch.float32, device=logits.device)
+    Tc = 0 if collab_idx is None else collab_idx.shape[1]
+    _check("c2r_route_from_logits", lib().c2r_route_from_logits(_ptr(logits), T, E, K, _ptr(collab_idx), Tc,
+                                                                 _ptr(idx), _ptr(gates), _stream()))
+    return idx, gates
+
+
+def permute(x, topk_idx, E, local_slot=None, E_local=None, ws=None, out=None, rows=True):
+    """Dispatch.  Returns (counts, offsets, perm, inv_perm, x_perm)."""
+    T, K = topk_idx.shape
+    dev = topk_idx.device
+    E_local = E if E_local is None else E_local
+    d = x.shape[1] if x is not None else 0
+    if out is None:
+        counts = torch.empty((E_local,), dtype=torch.int32, device=dev)
+        offsets = torch.empty((E_local + 1,), dtype=torch.int32, device=dev)
+        perm = torch.full((T * K,), -1, dtype=torch.int32, device=dev)
+        inv_perm = torch.empty((T * K,), dtype=torch.int32, device=dev)
+        x_perm = torch.empty((T * K, d), dtype=x.dtype, device=dev) if (rows and x is not None) else None
+    else:
+        counts, offsets, perm, inv_perm, x_perm = out
+    dt = _dt(x) if x is not None else F32
+    ws = _ws(workspace_bytes(STAGE_PERMUTE, T, d, E, K, 0, dt), dev, ws)
+    _check("c2r_permute", lib().c2r_permute(_ptr(x), dt, _ptr(topk_idx), T, d, E, K, _ptr(local_slot), E_local,
+                                            _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(x_perm),
+                                            _ptr(ws), ws.numel(), _stream()))
+    return counts, offsets, perm, inv_perm, x_perm
+
+
+def expert_ffn(x_perm, offsets, w_gate, w_up, w_down, ws=None, out=None):
+    """Grouped SwiGLU FFN over the rows of each expert.  Returns y_perm."""
+    A_cap, d = x_perm.shape
+    E_local, F, _ = w_gate.shape
+    assert offsets.numel() == E_local + 1 and offsets.dtype == torch.int32
+    assert w_up.shape == (E_local, F, d) and w_down.shape == (E_local, d, F)
+    assert w_gate.dtype == x_perm.dtype == w_up.dtype == w_down.dtype
+    y_perm = torch.empty_like(x_perm) if out is None else out
+    ws = _ws(workspace_bytes(STAGE_EXPERT_FFN, A_cap, d, E_local, 1, F, _dt(x_perm)), x_perm.device, ws)
+    _check("c2r_expert_ffn", lib().c2r_expert_ffn(_ptr(x_perm), _dt(x_perm), _ptr(offsets), E_local, A_cap, d, F,
+                                                  _ptr(w_gate), _ptr(w_up), _ptr(w_down), _ptr(y_perm), _ptr(ws),
+                                                  ws.numel(), _stream()))
+    return y_perm
+
+
+def expert_ffn_gate_up(x_perm, offsets, w_gate, w_up, h):
+    """First pass of the expert FFN: h = silu(x W_gate^T) * (x W_up^T)."""
+    A_cap, d = x_perm.shape
+    E_local, F, _ = w_gate.shape
+    assert h.shape == (A_cap, F) and h.dtype == x_perm.dtype
+    _check("c2r_expert_ffn_gate_up", lib().c2r_expert_ffn_gate_up(
+        _ptr(x_perm), _dt(x_perm), _ptr(offsets), E_local, A_cap, d, F, _ptr(w_gate), _ptr(w_up), _ptr(h), _stream()))
+    return h
+
+
+def expert_ffn_down(h, offsets, w_down, y_perm):
+    """Second pass of the expert FFN: y_perm = h W_down^T."""
+    A_cap, F = h.shape
+    E_local, d, _ = w_down.shape
+    assert y_perm.shape == (A_cap, d)
+    _check("c2r_expert_ffn_down", lib().c2r_expert_ffn_down(
+        _ptr(h), _dt(h), _ptr(offsets), E_local, A_cap, d, F, _ptr(w_down), _ptr(y_perm), _stream()))
+    return y_perm
+
+
+def combine(y_perm, gates, inv_perm, y_shared=None, out=None):
+    """Un-permute + gate-weighted sum.  Returns y[T, d]."""
+    T, K = gates.shape
+    d = y_perm.shape[1]
+    y = torch.empty((T, d), dtype=y_perm.dtype, device=y_perm.device) if out is None else out
+    _check("c2r_combine", lib().c2r_combine(_ptr(y_perm), _dt(y_perm), _ptr(gates), _ptr(inv_perm), T, d, K,
+                                            _ptr(y_shared), _ptr(y), _stream()))
+    return y
+
+
+class C2RLayer:
+    """One C2R MoE layer with all buffers allocated up front: forward() only
+    enqueues the library's stages on the current stream (no allocation, no sync)."""
+
+    def __init__(self, T, d, E, K, F, dtype, Wg, bias, collab_idx, w_gate, w_up, w_down,
+                 local_slot=None, E_local=None, shared=None, device="cuda"):
+        self.T, self.d, self.E, self.K, self.F = T, d, E, K, F
+        self.E_local = E if E_local is None else E_local
+        self.Wg, self.bias, self.collab_idx = Wg, bias, collab_idx
+        self.w = (w_gate, w_up, w_down)
+        self.local_slot, self.shared = local_slot, shared
+        dev = device
+        dt = F32 if dtype == torch.float32 else BF16
+        i32 = dict(dtype=torch.int32, device=dev)
+        self.idx = torch.empty((T, K), **i32)
+        self.gates = torch.empty((T, K), dtype=torch.float32, device=dev)
+        self.counts = torch.empty((self.E_local,), **i32)
+        self.offsets = torch.empty((self.E_local + 1,), **i32)
+        self.perm = torch.full((T * K,), -1, **i32)
+        self.inv_perm = torch.empty((T * K,), **i32)
+        self.x_perm = torch.empty((T * K, d), dtype=dtype, device=dev)
+        self.y_perm = torch.empty((T * K, d), dtype=dtype, device=dev)
+        self.y = torch.empty((T, d), dtype=dtype, device=dev)
+        u8 = dict(dtype=torch.uint8, device=dev)
+        self.ws_route = torch.empty(max(256, workspace_bytes(STAGE_ROUTE, T, d, E, K, 0, dt)), **u8)
+        self.ws_perm = torch.empty(max(256, workspace_bytes(STAGE_PERMUTE, T, d, E, K, 0, dt)), **u8)
+        self.ws_ffn = torch.empty(max(256, workspace_bytes(STAGE_EXPERT_FFN, T * K, d, self.E_local, 1, F, dt)), **u8)
+        if shared is not None:
+            Fs = shared[0].shape[1]
+            self.off_shared = torch.tensor([0, T], **i32)
+            self.y_shared = torch.empty((T, d), dtype=dtype, device=dev)
+            self.ws_shared = torch.empty(max(256, workspace_bytes(STAGE_EXPERT_FFN, T, d, 1, 1, Fs, dt)), **u8)
+        else:
+            self.y_shared = None
+
+    def forward(self, x):
+        route(x, self.Wg, self.bias, self.K, self.collab_idx, ws=self.ws_route, out=(self.idx, self.gates))
+        permute(x, self.idx, self.E, self.local_slot, self.E_local, ws=self.ws_perm,
+                out=(self.counts, self.offsets, self.perm, self.inv_perm, self.x_perm))
+        expert_ffn(self.x_perm, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
+        if self.shared is not None:
+            expert_ffn(x, self.off_shared, *self.shared, ws=self.ws_shared, out=self.y_shared)
+        return combine(self.y_perm, self.gates, self.inv_perm, self.y_shared, out=self.y)

@@ -1,0 +1,100 @@
+// Host entry points that do not belong to a single kernel file: version,
+// workspace query, and the expert-FFN dispatcher (fp32 vector path / bf16 MFMA path).
+#include "c2r_internal.h"
+
+namespace c2r {
+size_t route_workspace_bytes(int64_t T, int d, int E);
+size_t permute_workspace_bytes(int64_t T, int E, int K);
+int launch_ffn_f32_pass(int pass, const float *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
+                        int F, const float *b0, const float *b1, float *out, hipStream_t st);
+int launch_ffn_bf16_pass(int pass, const uint16_t *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
+                         int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out, hipStream_t st);
+}  // namespace c2r
+
+using namespace c2r;
+
+extern "C" int c2r_version(void) { return 100; }
+
+extern "C" size_t c2r_workspace_bytes(int stage, int64_t T, int d, int E, int K, int F, c2r_dtype dt) {
+    switch (stage) {
+        case C2R_STAGE_COACTIVATION:
+            return 0;
+        case C2R_STAGE_ROUTE:
+            return route_workspace_bytes(T, d, E);
+        case C2R_STAGE_PERMUTE:
+            return permute_workspace_bytes(T, E, K);
+        case C2R_STAGE_EXPERT_FFN: {
+            if (T <= 0 || F <= 0) return 0;
+            const size_t sz = dt == C2R_BF16 ? 2 : 4;
+            return round_up((size_t)T * (size_t)(K > 0 ? K : 1) * (size_t)F * sz, 256);
+        }
+        default:
+            return 0;
+    }
+}
+
+static int check_ffn(c2r_dtype dt, int E_local, int64_t A_cap, int d, int F) {
+    if (E_local < 1 || A_cap < 0 || d < 1 || F < 1) return C2R_ERR_INVALID_ARG;
+    if (dt != C2R_F32 && dt != C2R_BF16) return C2R_ERR_INVALID_ARG;
+    if (E_local > C2R_MAX_E) return C2R_ERR_UNSUPPORTED;
+    if (A_cap >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
+    if (d % 8 != 0 || F % 8 != 0) return C2R_ERR_UNSUPPORTED;
+    const size_t sz = dt == C2R_BF16 ? 2 : 4;
+    // 32-bit byte offsets are used inside one tile's rows and inside one expert's weights
+    if ((size_t)d * F * sz >= (1ull << 32) || 256ull * (d > F ? d : F) * sz >= (1ull << 32))
+        return C2R_ERR_UNSUPPORTED;
+    return C2R_OK;
+}
+
+static int ffn_pass(int pass, c2r_dtype dt, const void *a, const int32_t *offsets, int E_local, int64_t A_cap,
+                    int d, int F, const void *b0, const void *b1, void *out, void *stream) {
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (dt == C2R_BF16)
+        return launch_ffn_bf16_pass(pass, static_cast<const uint16_t *>(a), offsets, E_local, A_cap, d, F,
+                                    static_cast<const uint16_t *>(b0), static_cast<const uint16_t *>(b1),
+                                    static_cast<uint16_t *>(out), st);
+    return launch_ffn_f32_pass(pass, static_cast<const float *>(a), offsets, E_local, A_cap, d, F,
+                               static_cast<const float *>(b0), static_cast<const float *>(b1),
+                               static_cast<float *>(out), st);
+}
+
+extern "C" int c2r_expert_ffn_gate_up(const void *x_perm, c2r_dtype dt, const int32_t *offsets, int E_local,
+                                      int64_t A_cap, int d, int F, const void *w_gate, const void *w_up,
+                                      void *h, void *stream) {
+    const int rc = check_ffn(dt, E_local, A_cap, d, F);
+    if (rc != C2R_OK) return rc;
+    if (A_cap == 0) return C2R_OK;
+    if (!x_perm || !offsets || !w_gate || !w_up || !h) return C2R_ERR_INVALID_ARG;
+    if (!aligned(x_perm, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(h, 16))
+        return C2R_ERR_INVALID_ARG;
+    return ffn_pass(0, dt, x_perm, offsets, E_local, A_cap, d, F, w_gate, w_up, h, stream);
+}
+
+extern "C" int c2r_expert_ffn_down(const void *h, c2r_dtype dt, const int32_t *offsets, int E_local,
+                                   int64_t A_cap, int d, int F, const void *w_down, void *y_perm,
+                                   void *stream) {
+    const int rc = check_ffn(dt, E_local, A_cap, d, F);
+    if (rc != C2R_OK) return rc;
+    if (A_cap == 0) return C2R_OK;
+    if (!h || !offsets || !w_down || !y_perm) return C2R_ERR_INVALID_ARG;
+    if (!aligned(h, 16) || !aligned(w_down, 16) || !aligned(y_perm, 16)) return C2R_ERR_INVALID_ARG;
+    return ffn_pass(1, dt, h, offsets, E_local, A_cap, d, F, w_down, nullptr, y_perm, stream);
+}
+
+extern "C" int c2r_expert_ffn(const void *x_perm, c2r_dtype dt, const int32_t *offsets, int E_local,
+                              int64_t A_cap, int d, int F, const void *w_gate, const void *w_up,
+                              const void *w_down, void *y_perm, void *ws, size_t ws_bytes,
+                              void *stream) {
+    int rc = check_ffn(dt, E_local, A_cap, d, F);
+    if (rc != C2R_OK) return rc;
+    if (A_cap == 0) return C2R_OK;
+    if (!x_perm || !offsets || !w_gate || !w_up || !w_down || !y_perm) return C2R_ERR_INVALID_ARG;
+    if (!aligned(x_perm, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(w_down, 16) ||
+        !aligned(y_perm, 16))
+        return C2R_ERR_INVALID_ARG;
+    const size_t need = round_up((size_t)A_cap * F * (dt == C2R_BF16 ? 2 : 4), 256);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return C2R_ERR_WORKSPACE;
+    rc = ffn_pass(0, dt, x_perm, offsets, E_local, A_cap, d, F, w_gate, w_up, ws, stream);
+    if (rc != C2R_OK) return rc;
+    return ffn_pass(1, dt, ws, offsets, E_local, A_cap, d, F, w_down, nullptr, y_perm, stream);
+}

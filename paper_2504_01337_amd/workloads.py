@@ -70,13 +70,20 @@ def _rng(w: Workload, tensor_id: int) -> np.random.Generator:
     return np.random.default_rng(SEED_BASE + 1000 * w.cfg_id + tensor_id)
 
 
-def round_bf16(a: np.ndarray) -> np.ndarray:
-    """Round fp32 values to the nearest bf16 (ties to even), returned as fp32."""
+def round_bf16_reference(a: np.ndarray) -> np.ndarray:
+    """Round fp32 values to the nearest bf16 (ties to even), returned as fp32 (bit twiddling)."""
     a = np.ascontiguousarray(a, dtype=np.float32)
     u = a.view(np.uint32)
     r = ((u >> 16) & 1) + np.uint32(0x7FFF)
     out = ((u + r) & np.uint32(0xFFFF0000)).astype(np.uint32)
     return out.view(np.float32)
+
+
+def round_bf16(a: np.ndarray) -> np.ndarray:
+    """Same rounding through torch's multi-threaded CPU cast (finite inputs)."""
+    import torch
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return torch.from_numpy(a).to(torch.bfloat16).to(torch.float32).numpy()
 
 
 def to_bf16_bits(a: np.ndarray) -> np.ndarray:

@@ -1,0 +1,227 @@
+"""GPU parity, stage by stage: every entry point of the C ABI against the CPU
+oracle on the same seeded inputs.  Integer results are compared bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2504_01337_amd import workloads as wl
+from helpers import dev, host, max_rel_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def c2r():
+    from paper_2504_01337_amd import c2r as m
+    m.lib()
+    assert torch.cuda.is_available()
+    return m
+
+
+def _collab(E, Tc, seed):
+    rng = np.random.default_rng(seed)
+    out = np.empty((E, Tc), dtype=np.int32)
+    for i in range(E):
+        others = np.array([j for j in range(E) if j != i])
+        out[i] = rng.permutation(others)[:Tc]
+    return out
+
+
+def _check_route(c2r, orc, x, Wg, bias, K, collab, dtype, bit_exact_logits=True):
+    idx, gates, logits = c2r.route(dev(x, dtype), dev(Wg), dev(bias), K,
+                                   None if collab is None else dev(collab), want_logits=True)
+    torch.cuda.synchronize()
+    l_ref = orc.logits_canon_f32(x, Wg, bias)
+    l_gpu = host(logits)
+    if bit_exact_logits:
+        assert np.array_equal(l_gpu.view(np.uint32), l_ref.view(np.uint32)), \
+            f"logit bits differ in {(l_gpu != l_ref).sum()} places"
+    idx_ref, g_ref = orc.route(l_gpu, K, collab)          # stage-wise: the GPU's own logits
+    assert np.array_equal(host(idx), idx_ref)
+    np.testing.assert_allclose(host(gates), g_ref, rtol=2e-6, atol=1e-7)
+    l64 = orc.logits_f64(x, Wg, bias)
+    assert np.abs(l_gpu - l64).max() <= 1e-5 * max(np.abs(l64).max(), 1.0)
+    return host(idx)
+
+
+@pytest.mark.parametrize("name,T", [("C1", 512), ("C2", 700), ("C3", 1000), ("C5", 333)])
+def test_route_workload_shapes(c2r, orc, name, T):
+    w = wl.scaled(wl.WORKLOADS[name], T=T)
+    x = wl.hidden(w)
+    Wg, bias = wl.router(w)
+    collab = _collab(w.E, w.Tc, 1)
+    _check_route(c2r, orc, x, Wg, bias, w.K, collab, w.dtype)
+    _check_route(c2r, orc, x, Wg, bias, w.K, None, w.dtype)            # conventional top-K
+
+
+@pytest.mark.parametrize("E,K,Tc,d,T,dtype", [
+    (8, 2, 4, 256, 512, "f32"), (60, 4, 16, 2048, 777, "bf16"), (64, 8, 20, 512, 130, "bf16"),
+    (5, 2, 3, 64, 65, "f32"), (13, 13, 12, 136, 1, "bf16"), (7, 1, 0, 264, 63, "bf16"),
+    (33, 3, 2, 1000, 257, "f32")])
+def test_route_exact_arithmetic_ties(c2r, orc, E, K, Tc, d, T, dtype):
+    # integer / dyadic inputs: logits exact in any order, ties frequent -> tie rule and masks
+    x, Wg = wl.exact_arithmetic_router(T, d, E, seed=E + K)
+    collab = _collab(E, Tc, 2) if Tc > 0 else None
+    idx = _check_route(c2r, orc, x, Wg, None, K, collab, dtype)
+    exact = (x.astype(np.int64) @ np.round(Wg * 8).astype(np.int64)).astype(np.float64) / 8.0
+    l_ref = orc.logits_canon_f32(x, Wg)
+    assert np.array_equal(l_ref.astype(np.float64), exact)
+    if collab is not None:
+        for t in range(T):
+            assert set(idx[t, 1:]) <= set(collab[idx[t, 0]])
+
+
+def test_route_full_list_is_topk(c2r, orc):
+    # Fig. 3 caption: a list of all other experts removes the constraint
+    w = wl.scaled(wl.WORKLOADS["C1"], T=300)
+    x = wl.hidden(w)
+    Wg, _ = wl.router(w)
+    full = np.array([[j for j in range(w.E) if j != i] for i in range(w.E)], dtype=np.int32)
+    a = c2r.route(dev(x), dev(Wg), None, w.K, dev(full))
+    b = c2r.route(dev(x), dev(Wg), None, w.K, None)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_route_short_or_bad_list_entries(c2r, orc):
+    # duplicate / self / out-of-range entries are ignored; an unfillable slot gets -1 and gate 0
+    E, K = 8, 3
+    x, Wg = wl.exact_arithmetic_router(100, 64, E, seed=3)
+    collab = np.array([[i, (i + 1) % E, (i + 1) % E, 99] for i in range(E)], dtype=np.int32)
+    idx, gates, _ = c2r.route(dev(x), dev(Wg), None, K, dev(collab))
+    idx, gates = host(idx), host(gates)
+    l = orc.logits_canon_f32(x, Wg)
+    assert np.array_equal(idx[:, 0], np.argmax(l, axis=1))
+    assert np.array_equal(idx[:, 1], (idx[:, 0] + 1) % E)
+    assert np.all(idx[:, 2] == -1) and np.all(gates[:, 2] == 0)
+    np.testing.assert_allclose(gates.sum(1), 1.0, rtol=1e-6)
+
+
+@pytest.mark.parametrize("E,K,Tc,T", [(60, 4, 16, 5000), (7, 2, 3, 63), (64, 4, 8, 257), (16, 4, 8, 1)])
+def test_route_from_logits(c2r, orc, E, K, Tc, T):
+    rng = np.random.default_rng(E)
+    logits = rng.integers(-5, 6, size=(T, E)).astype(np.float32)       # many ties
+    logits[::7] += rng.standard_normal((len(logits[::7]), E)).astype(np.float32)
+    collab = _collab(E, Tc, 3)
+    for ci in (collab, None):
+        idx, gates = c2r.route_from_logits(dev(logits), K, None if ci is None else dev(ci))
+        idx_ref, g_ref = orc.route(logits, K, ci)
+        assert np.array_equal(host(idx), idx_ref)
+        np.testing.assert_allclose(host(gates), g_ref, rtol=2e-6, atol=1e-7)
+
+
+def test_route_nan_logits_follow_the_stated_rule(c2r, orc):
+    E, K = 12, 3
+    logits = np.random.default_rng(5).standard_normal((200, E)).astype(np.float32)
+    logits[::3, 0] = np.nan
+    logits[1::5, 7] = np.nan
+    logits[10] = np.nan
+    idx, _ = c2r.route_from_logits(dev(logits), K, None)
+    idx_ref, _ = orc.route(logits, K, None)
+    assert np.array_equal(host(idx), idx_ref)
+
+
+@pytest.mark.parametrize("E,K,T", [(8, 2, 512), (16, 4, 1000), (60, 4, 70001), (64, 6, 129), (33, 3, 64)])
+def test_coactivation(c2r, orc, E, K, T):
+    rng = np.random.default_rng(E + T)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[:, : E // 3] += 1.5                                          # skewed load
+    idx, _ = orc.route(logits, K)
+    idx[::11, K - 1] = -1                                               # padded slots are ignored
+    Cg = c2r.build_coactivation(dev(idx), E)
+    assert np.array_equal(host(Cg).astype(np.int64), orc.coactivation(idx, E))
+    # accumulate a second batch into the same matrix
+    c2r.build_coactivation(dev(idx[: T // 2]), E, Cg)
+    assert np.array_equal(host(Cg).astype(np.int64),
+                          orc.coactivation(idx[: T // 2], E, orc.coactivation(idx, E)))
+    M = host(Cg)
+    assert np.array_equal(M, M.T)
+
+
+@pytest.mark.parametrize("E", [2, 8, 60, 64])
+def test_collaborators(c2r, orc, E):
+    rng = np.random.default_rng(E)
+    Cm = rng.integers(0, 4, size=(E, E))
+    Cm = Cm + Cm.T
+    if E > 4:
+        Cm[3, :] = 0
+        Cm[:, 3] = 0
+    np.fill_diagonal(Cm, 10 ** 6)
+    for Tc in sorted({1, min(4, E - 1), E - 1, E + 3}):
+        ci, mask = c2r.collaborators(dev(Cm.astype(np.int32)), Tc)
+        ref = orc.collaborators(Cm, Tc)
+        assert np.array_equal(host(ci), ref)
+        m = host(mask).astype(np.uint64)
+        for i in range(E):
+            assert int(m[i]) == sum(1 << int(j) for j in ref[i])
+
+
+@pytest.mark.parametrize("E,K,T,d,dtype,local", [
+    (8, 2, 512, 256, "f32", None), (60, 4, 3001, 64, "bf16", None), (60, 4, 5000, 128, "bf16", 15),
+    (16, 4, 1, 64, "bf16", None), (64, 1, 1025, 72, "f32", 7), (5, 5, 300, 8, "f32", None)])
+def test_permute(c2r, orc, E, K, T, d, dtype, local):
+    rng = np.random.default_rng(E * 7 + T)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[:, 0] += 2.0
+    idx, _ = orc.route(logits, K)
+    x = rng.standard_normal((T, d)).astype(np.float32)
+    if dtype == "bf16":
+        x = wl.round_bf16(x)
+    ls, E_local = None, E
+    if local:
+        ls = np.full(E, -1, dtype=np.int32)
+        chosen = np.sort(rng.permutation(E)[:local])
+        ls[chosen] = rng.permutation(local).astype(np.int32)            # arbitrary renumbering
+        E_local = local
+    counts, offsets, perm, inv, x_perm = c2r.permute(dev(x, dtype), dev(idx), E, dev(ls), E_local)
+    rc, ro, rp, ri = orc.permute(idx, E, ls, E_local)
+    assert np.array_equal(host(counts), rc) and np.array_equal(host(offsets), ro)
+    n = int(ro[-1])
+    assert np.array_equal(host(perm)[:n], rp) and np.all(host(perm)[n:] == -1)
+    assert np.array_equal(host(inv), ri)
+    assert np.array_equal(host(x_perm)[:n], x[rp // K])                 # pure copy: bit exact
+
+
+@pytest.mark.parametrize("dtype,d,F,sizes", [
+    ("f32", 64, 96, [5, 0, 70, 1, 130]), ("f32", 256, 512, [100, 300, 0, 3]),
+    ("bf16", 128, 256, [300, 0, 1, 64, 257, 5]), ("bf16", 64, 88, [33, 700]),
+    ("bf16", 256, 688, [12, 0, 0, 513]), ("bf16", 2048, 128, [40, 260])])
+def test_expert_ffn_ragged_groups(c2r, orc, dtype, d, F, sizes):
+    rng = np.random.default_rng(d + F)
+    E = len(sizes)
+    offsets = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int32)
+    n = int(offsets[-1])
+    cap = n + 37                                                         # capacity beyond the used rows
+    store = wl.round_bf16 if dtype == "bf16" else (lambda a: a)
+    x = store(rng.standard_normal((cap, d)).astype(np.float32))
+    wg = store((rng.standard_normal((E, F, d)) * 0.05).astype(np.float32))
+    wu = store((rng.standard_normal((E, F, d)) * 0.05).astype(np.float32))
+    wd = store((rng.standard_normal((E, d, F)) * 0.05).astype(np.float32))
+    sentinel = 123.0
+    y = torch.full((cap, d), sentinel, dtype=torch.bfloat16 if dtype == "bf16" else torch.float32, device="cuda")
+    c2r.expert_ffn(dev(x, dtype), dev(offsets), dev(wg, dtype), dev(wu, dtype), dev(wd, dtype), out=y)
+    torch.cuda.synchronize()
+    yh = host(y)
+    eor = np.repeat(np.arange(E), sizes).astype(np.int32)
+    ref = orc.expert_ffn_rows(x[:n], eor, wg, wu, wd)
+    assert max_rel_err(yh[:n], ref) <= (1e-2 if dtype == "bf16" else 1e-5)
+    assert np.all(yh[n:] == sentinel)                                   # rows past the last group untouched
+
+
+@pytest.mark.parametrize("dtype,T,K,d", [("f32", 100, 2, 64), ("bf16", 1000, 4, 2048), ("bf16", 3, 1, 8)])
+def test_combine(c2r, orc, dtype, T, K, d):
+    rng = np.random.default_rng(T)
+    store = wl.round_bf16 if dtype == "bf16" else (lambda a: a)
+    E = 9
+    idx, g = orc.route(rng.standard_normal((T, E)).astype(np.float32), K)
+    ls = np.arange(E, dtype=np.int32)
+    ls[4] = -1
+    ls[5:] -= 1
+    _, _, perm, inv = orc.permute(idx, E, ls, E - 1)
+    yp = store(rng.standard_normal((T * K, d)).astype(np.float32))
+    ys = store(rng.standard_normal((T, d)).astype(np.float32))
+    g32 = g.astype(np.float32)
+    for shared in (None, ys):
+        y = c2r.combine(dev(yp, dtype), dev(g32), dev(inv), None if shared is None else dev(shared, dtype))
+        ref = orc.combine(yp, g32, inv, T, K, shared)
+        tol = 2.0 ** -8 if dtype == "bf16" else 1e-6                    # one rounding of the result
+        assert np.abs(host(y) - ref).max() <= tol * max(np.abs(ref).max(), 1.0)
