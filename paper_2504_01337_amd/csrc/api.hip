@@ -9,9 +9,23 @@ int launch_ffn_f32_pass(int pass, const float *a, const int32_t *offsets, int E_
                         int F, const float *b0, const float *b1, float *out, hipStream_t st);
 int launch_ffn_bf16_pass(int pass, const uint16_t *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
                          int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out, hipStream_t st);
+int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t *offsets, int E_local,
+                             int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1,
+                             uint16_t *out, int ldo, hipStream_t st);
 }  // namespace c2r
 
 using namespace c2r;
+
+// Row pitch of the hidden activation h inside the library's own workspace: padded to the
+// k-slice of the fast bf16 path (the padding is kept at zero by the first pass).
+static bool fast_bf16(c2r_dtype dt, int d, int F) {
+    // the copy-engine kernel: bf16 and a model width of whole 64-element k-slices (F is
+    // padded to such slices inside the workspace)
+    (void)F;
+    return dt == C2R_BF16 && d % 64 == 0;
+}
+
+static int h_pitch(c2r_dtype dt, int d, int F) { return fast_bf16(dt, d, F) ? (F + 63) / 64 * 64 : F; }
 
 extern "C" int c2r_version(void) { return 100; }
 
@@ -26,7 +40,7 @@ extern "C" size_t c2r_workspace_bytes(int stage, int64_t T, int d, int E, int K,
         case C2R_STAGE_EXPERT_FFN: {
             if (T <= 0 || F <= 0) return 0;
             const size_t sz = dt == C2R_BF16 ? 2 : 4;
-            return round_up((size_t)T * (size_t)(K > 0 ? K : 1) * (size_t)F * sz, 256);
+            return round_up((size_t)T * (size_t)(K > 0 ? K : 1) * (size_t)h_pitch(dt, d, F) * sz, 256);
         }
         default:
             return 0;
@@ -46,9 +60,17 @@ static int check_ffn(c2r_dtype dt, int E_local, int64_t A_cap, int d, int F) {
     return C2R_OK;
 }
 
+// ldh: pitch of h (output of pass 0, input of pass 1).  The copy-engine path needs the
+// contraction rows of A padded to a multiple of 64 elements.
 static int ffn_pass(int pass, c2r_dtype dt, const void *a, const int32_t *offsets, int E_local, int64_t A_cap,
-                    int d, int F, const void *b0, const void *b1, void *out, void *stream) {
+                    int d, int F, int ldh, const void *b0, const void *b1, void *out, void *stream) {
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (fast_bf16(dt, d, F) && ldh % 64 == 0)
+        return launch_ffn_bf16_dma_pass(pass, static_cast<const uint16_t *>(a), pass == 0 ? d : ldh, offsets,
+                                        E_local, A_cap, d, F, static_cast<const uint16_t *>(b0),
+                                        static_cast<const uint16_t *>(b1), static_cast<uint16_t *>(out),
+                                        pass == 0 ? ldh : d, st);
+    if (ldh != F) return C2R_ERR_UNSUPPORTED;
     if (dt == C2R_BF16)
         return launch_ffn_bf16_pass(pass, static_cast<const uint16_t *>(a), offsets, E_local, A_cap, d, F,
                                     static_cast<const uint16_t *>(b0), static_cast<const uint16_t *>(b1),
@@ -67,7 +89,7 @@ extern "C" int c2r_expert_ffn_gate_up(const void *x_perm, c2r_dtype dt, const in
     if (!x_perm || !offsets || !w_gate || !w_up || !h) return C2R_ERR_INVALID_ARG;
     if (!aligned(x_perm, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(h, 16))
         return C2R_ERR_INVALID_ARG;
-    return ffn_pass(0, dt, x_perm, offsets, E_local, A_cap, d, F, w_gate, w_up, h, stream);
+    return ffn_pass(0, dt, x_perm, offsets, E_local, A_cap, d, F, F, w_gate, w_up, h, stream);
 }
 
 extern "C" int c2r_expert_ffn_down(const void *h, c2r_dtype dt, const int32_t *offsets, int E_local,
@@ -78,7 +100,7 @@ extern "C" int c2r_expert_ffn_down(const void *h, c2r_dtype dt, const int32_t *o
     if (A_cap == 0) return C2R_OK;
     if (!h || !offsets || !w_down || !y_perm) return C2R_ERR_INVALID_ARG;
     if (!aligned(h, 16) || !aligned(w_down, 16) || !aligned(y_perm, 16)) return C2R_ERR_INVALID_ARG;
-    return ffn_pass(1, dt, h, offsets, E_local, A_cap, d, F, w_down, nullptr, y_perm, stream);
+    return ffn_pass(1, dt, h, offsets, E_local, A_cap, d, F, F, w_down, nullptr, y_perm, stream);
 }
 
 extern "C" int c2r_expert_ffn(const void *x_perm, c2r_dtype dt, const int32_t *offsets, int E_local,
@@ -92,9 +114,10 @@ extern "C" int c2r_expert_ffn(const void *x_perm, c2r_dtype dt, const int32_t *o
     if (!aligned(x_perm, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(w_down, 16) ||
         !aligned(y_perm, 16))
         return C2R_ERR_INVALID_ARG;
-    const size_t need = round_up((size_t)A_cap * F * (dt == C2R_BF16 ? 2 : 4), 256);
+    const int ldh = h_pitch(dt, d, F);
+    const size_t need = round_up((size_t)A_cap * ldh * (dt == C2R_BF16 ? 2 : 4), 256);
     if (!ws || ws_bytes < need || !aligned(ws, 256)) return C2R_ERR_WORKSPACE;
-    rc = ffn_pass(0, dt, x_perm, offsets, E_local, A_cap, d, F, w_gate, w_up, ws, stream);
+    rc = ffn_pass(0, dt, x_perm, offsets, E_local, A_cap, d, F, ldh, w_gate, w_up, ws, stream);
     if (rc != C2R_OK) return rc;
-    return ffn_pass(1, dt, ws, offsets, E_local, A_cap, d, F, w_down, nullptr, y_perm, stream);
+    return ffn_pass(1, dt, ws, offsets, E_local, A_cap, d, F, ldh, w_down, nullptr, y_perm, stream);
 }

@@ -9,7 +9,8 @@
 // of the same f range, and every wave owns matching gate / up fragments, so the
 // SwiGLU product is formed in registers and only h (bf16) is written.
 //
-// Tiling: 256 threads = 4 waves as WM x WN; v_mfma_f32_32x32x16_bf16; a BM x BN x BK
+// Tiling: WM x WN waves per workgroup (two per SIMD, so one wave's loads and address
+// arithmetic overlap the other's MFMAs); v_mfma_f32_32x32x16_bf16; a BM x BN x BK
 // tile per step, double buffered in LDS with 16-byte chunks XOR-swizzled by row so
 // that both the staging writes and the fragment reads are bank-conflict free.
 // Global loads for step k+1 are issued before the MFMAs of step k.
@@ -20,23 +21,21 @@
 
 namespace c2r {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-
 template <int MODE, int BM, int BN, int BK, int WM, int WN>
-__global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t *__restrict__ A, int lda,
+__global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_kernel(const uint16_t *__restrict__ A, int lda,
                                                        const int32_t *__restrict__ offsets,
                                                        int E_local, int A_cap, int N, int Kdim,
                                                        const uint16_t *__restrict__ B0,
                                                        const uint16_t *__restrict__ B1,
                                                        uint16_t *__restrict__ out, int ldo, int ntn) {
-    static_assert(WM * WN == 4, "four waves");
+    constexpr int NT = WM * WN * 64;  // threads per workgroup
     constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
     constexpr int FM = TM / 32, FN = TN / 32;  // 32x32 fragments per wave
     constexpr int CPR = BK / 8;                // 16-byte chunks per tile row
     constexpr int ROWB = BK * 2;               // bytes per tile row
-    constexpr int NA = BM * CPR / 256, NB = BN * CPR / 256;
-    constexpr int RSTEP = 256 / CPR;           // tile rows covered by one pass of the loader
+    constexpr int NA = BM * CPR / NT, NB = BN * CPR / NT;
+    constexpr int RSTEP = NT / CPR;            // tile rows covered by one pass of the loader
+    static_assert(CPR == 8 && RSTEP % 16 == 0, "swizzle key uses row bits 0..3");
     constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
     constexpr int BNF = MODE == 0 ? BN / 2 : BN;  // output columns per tile
     static_assert(MODE == 1 || FN % 2 == 0, "gate/up fragments pair up");
@@ -47,13 +46,10 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t *__restric
 
     // ---- which tile ----
     GroupTile g = find_group_tile<BM>(offsets, E_local, A_cap, -1);
-    const int total = g.total_mtiles * ntn;
-    const int per_xcd = (total + 7) / 8;
-    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tile = xcd * per_xcd + slot;
-    if (slot >= per_xcd || tile >= total) return;
-    const int mt = tile / ntn, nt = tile - mt * ntn;
-    g = find_group_tile<BM>(offsets, E_local, A_cap, mt);
+    const TileId tl = xcd_grouped_tile(g.total_mtiles, ntn);
+    if (!tl.valid) return;
+    const int nt = tl.nt;
+    g = find_group_tile<BM>(offsets, E_local, A_cap, tl.mt);
     if (g.expert < 0) return;
     const int n0 = nt * BNF;
     const int rows = g.row_end - g.row_begin;  // >= 1; may exceed BM
@@ -78,7 +74,7 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t *__restric
         c = c < N ? c : N - 1;
         offB[i] = (uint32_t)c * (uint32_t)Kdim * 2u + lc * 16u;
     }
-    const uint32_t lds_w = (uint32_t)lr * ROWB + ((lc ^ (lr & (CPR - 1))) * 16u);
+    const uint32_t lds_w = (uint32_t)lr * ROWB + ((lc ^ swz_key(lr)) * 16u);
 
     uint4 ra[NA], rb[NB];
     auto gload = [&](int k0) {
@@ -109,7 +105,7 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t *__restric
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    // fragment read addresses (row part); rows are multiples of 32 plus lane%32, so row & 7 = lane & 7
+    // fragment read addresses (row part); rows are multiples of 32 plus lane%32, so the key is the lane's
     const int fr = lane & 31, fh = lane >> 5;
     uint32_t rdA[FM], rdB[FN];
 #pragma unroll
@@ -123,7 +119,20 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t *__restric
             r = wn * TN + j * 32;
         rdB[j] = (uint32_t)(r + fr) * ROWB;
     }
-    const int sw = fr & (CPR - 1);
+    const int sw = swz_key(fr);
+    // rows of this wave's M range that exist (wave-uniform): fragments past the group's
+    // end are never multiplied
+    const int wrows = __builtin_amdgcn_readfirstlane(rows - wm * TM);
+
+    constexpr int NKK = BK / 16;
+    bf16x8 af[2][FM], bfr[2][FN];
+    auto read_frags = [&](const unsigned char *sa, const unsigned char *sb, int kk, int set) {
+        const uint32_t ch = (uint32_t)(((kk * 2 + fh) ^ sw) * 16);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) af[set][i] = *reinterpret_cast<const bf16x8 *>(sa + rdA[i] + ch);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bfr[set][j] = *reinterpret_cast<const bf16x8 *>(sb + rdB[j] + ch);
+    };
 
     const int nk = (Kdim + BK - 1) / BK;
     gload(0);
@@ -131,46 +140,56 @@ __global__ __launch_bounds__(256) void ffn_bf16_kernel(const uint16_t *__restric
     __syncthreads();
     for (int kt = 0; kt < nk; ++kt) {
         const int cur = kt & 1;
-        if (kt + 1 < nk) gload((kt + 1) * BK);
         const unsigned char *sa = smem + cur * (A_BYTES + B_BYTES);
         const unsigned char *sb = sa + A_BYTES;
+        read_frags(sa, sb, 0, 0);
+        if (kt + 1 < nk) gload((kt + 1) * BK);
 #pragma unroll
-        for (int kk = 0; kk < BK / 16; ++kk) {
-            const uint32_t ch = (uint32_t)(((kk * 2 + fh) ^ sw) * 16);
-            bf16x8 af[FM], bfr[FN];
+        for (int kk = 0; kk < NKK; ++kk) {
+            // fetch the next k-slice's fragments before this slice's MFMAs are issued
+            if (kk + 1 < NKK) read_frags(sa, sb, kk + 1, (kk + 1) & 1);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int i = 0; i < FM; ++i) af[i] = *reinterpret_cast<const bf16x8 *>(sa + rdA[i] + ch);
+            for (int i = 0; i < FM; ++i) {
+                if (i * 32 < wrows) {
 #pragma unroll
-            for (int j = 0; j < FN; ++j) bfr[j] = *reinterpret_cast<const bf16x8 *>(sb + rdB[j] + ch);
-#pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    for (int j = 0; j < FN; ++j)  // operands swapped: the lane's 4-element runs lie along n
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[kk & 1][j], af[kk & 1][i],
+                                                                            acc[i][j], 0, 0, 0);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         if (kt + 1 < nk) lstore(cur ^ 1);
         __syncthreads();
     }
 
-    // ---- epilogue: lane holds rows 8*(v/4) + 4*(lane/32) + v%4 of column lane%32 of each fragment ----
+    // ---- epilogue.  Fragment (i, j) holds C^T: lane (fr, fh), register v is
+    //      row m = i*32 + fr, column n = j*32 + 8*(v/4) + 4*fh + v%4  -> 8-byte stores ----
     uint16_t *outb = out + (size_t)g.row_begin * ldo;
     constexpr int FJ = MODE == 0 ? FN / 2 : FN;
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
+        const int r = wm * TM + i * 32 + fr;
+        if (r >= rows) continue;
 #pragma unroll
         for (int j = 0; j < FJ; ++j) {
-            const int col = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN) + j * 32 + fr;
-            if (col >= N) continue;
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int r = wm * TM + i * 32 + (v >> 2) * 8 + fh * 4 + (v & 3);
-                if (r >= rows) continue;
-                float val;
-                if (MODE == 0)
-                    val = silu_mul(acc[i][j][v], acc[i][j + FN / 2][v]);
-                else
-                    val = acc[i][j][v];
-                outb[(size_t)r * ldo + col] = (uint16_t)f32_to_bf16_bits(val);
+            for (int q = 0; q < 4; ++q) {
+                const int col = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN) + j * 32 + q * 8 + fh * 4;
+                if (col >= N) continue;  // N and col are multiples of 4
+                float v4[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (MODE == 0)
+                        v4[u] = silu_mul(acc[i][j][q * 4 + u], acc[i][j + FN / 2][q * 4 + u]);
+                    else
+                        v4[u] = acc[i][j][q * 4 + u];
+                }
+                uint2 pk;
+                pk.x = pack_bf16x2(v4[0], v4[1]);
+                pk.y = pack_bf16x2(v4[2], v4[3]);
+                *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
             }
         }
     }
@@ -184,17 +203,17 @@ static int launch_cfg(int pass, const uint16_t *a, const int32_t *offsets, int E
     const int64_t grid = (mtiles * ntn + 7) / 8 * 8;
     if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (pass == 0)
-        ffn_bf16_kernel<0, BM, BN, BK, WM, WN><<<dim3((unsigned)grid), dim3(256), 0, st>>>(
+        ffn_bf16_kernel<0, BM, BN, BK, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(
             a, d, offsets, E_local, (int)A_cap, F, d, b0, b1, out, F, ntn);
     else
-        ffn_bf16_kernel<1, BM, BN, BK, WM, WN><<<dim3((unsigned)grid), dim3(256), 0, st>>>(
+        ffn_bf16_kernel<1, BM, BN, BK, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(
             a, F, offsets, E_local, (int)A_cap, d, F, b0, nullptr, out, d, ntn);
     return launch_status();
 }
 
 int launch_ffn_bf16_pass(int pass, const uint16_t *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
                          int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out, hipStream_t st) {
-    return launch_cfg<256, 256, 64, 2, 2>(pass, a, offsets, E_local, A_cap, d, F, b0, b1, out, st);
+    return launch_cfg<256, 256, 64, 2, 4>(pass, a, offsets, E_local, A_cap, d, F, b0, b1, out, st);
 }
 
 }  // namespace c2r

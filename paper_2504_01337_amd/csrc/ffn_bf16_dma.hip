@@ -1,0 +1,261 @@
+// Grouped SwiGLU expert FFN in bf16, fast path: global -> LDS copies that bypass the
+// register file (global_load_lds_dwordx4), 8 waves per workgroup, 256 x 256 output tiles,
+// 64-wide k-slices double buffered in LDS.
+//
+// Same two passes, tile numbering and epilogue as the generic kernel in ffn_bf16.hip;
+// what differs is how a k-slice reaches LDS.  One wave-level copy instruction moves
+// 64 x 16 bytes = 8 tile rows of 128 bytes, i.e. whole cache lines (measured: 128-byte
+// rows copy at ~25 TB/s chip-wide, 64-byte rows at ~16 TB/s, and prefetch depth beyond
+// one slice buys nothing).  Lane l lands at byte 16*l of the 1 KB run, i.e. row l/8, chunk
+// position l%8, so the lane fetches the global chunk (l%8) ^ swz_key(row) and the
+// swizzled layout falls out without any LDS write instruction.  The copy of slice k+1
+// is asynchronous and overlaps the MFMAs of slice k; one "my copies landed" wait + bare
+// barrier per slice hands the stage over.
+//
+// Contract (checked by the launcher): the contraction length seen by A is padded to a
+// multiple of 64 with zeros (lda >= 64 * ceil(K/64)); a B chunk past K is re-read from
+// chunk 0 of the same row and multiplied by those zeros.
+#include "ffn_common.h"
+
+namespace c2r {
+
+// 16 bytes per lane, global -> LDS, without passing through registers.  `lds` is the
+// wave-uniform start of the 1024-byte run; lane l's data lands at lds + 16*l.
+// Written as inline assembly on purpose: when the compiler sees the copy as an LDS write
+// it guards later LDS reads with vmcnt(0) whenever its alias bookkeeping loses track
+// (it does across this kernel's unrolled ring), which serialises the pipeline.  Hidden
+// from it, the only waits on copies are the ones this file states (wait_copies_but).
+__device__ __forceinline__ void copy16_to_lds(const unsigned char *gsrc, unsigned char *lds) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    asm volatile(
+        "s_mov_b32 m0, %1\n\t"
+        "s_nop 0\n\t"
+        "global_load_lds_dwordx4 %0, off"
+        :
+        : "v"(gsrc), "s"(lds_addr)
+        : "memory", "m0");
+#endif
+}
+
+// Wait until at most N of this wave's copies are still in flight (they complete in order);
+// the other counters are left alone.
+template <int N>
+__device__ __forceinline__ void wait_copies_but() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+#endif
+}
+
+// Bare workgroup barrier.  __syncthreads() (and any workgroup fence) also drains every
+// outstanding copy (vmcnt(0)), which would serialise the slices in flight; here the
+// caller states exactly which copies must have landed (wait_copies_but) and the
+// scheduling fences keep the compiler from moving LDS reads across the barrier.
+__device__ __forceinline__ void lds_barrier() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_sched_barrier(0);
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_sched_barrier(0);
+#endif
+}
+
+template <int MODE, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
+    const uint16_t *__restrict__ A, int lda, const int32_t *__restrict__ offsets, int E_local,
+    int A_cap, int N, int Kdim, const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
+    uint16_t *__restrict__ out, int ldo, int ntn, int zero_to) {
+    constexpr int BM = 256, BN = 256, BK = 64;
+    constexpr int NW = WM * WN;                // waves
+    constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
+    constexpr int FM = TM / 32, FN = TN / 32;  // 32x32 fragments per wave
+    constexpr int ROWB = BK * 2;               // 128 bytes per tile row: whole cache lines per copy
+    constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;  // 8-row copy groups per wave
+    constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
+    constexpr int BNF = MODE == 0 ? BN / 2 : BN;
+    constexpr int NKK = BK / 16;
+    static_assert(MODE == 1 || FN % 2 == 0, "gate/up fragments pair up");
+    static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "copy groups divide evenly");
+    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE_BYTES];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+
+    GroupTile g = find_group_tile<BM>(offsets, E_local, A_cap, -1);
+    const TileId tl = xcd_grouped_tile(g.total_mtiles, ntn);
+    if (!tl.valid) return;
+    g = find_group_tile<BM>(offsets, E_local, A_cap, tl.mt);
+    if (g.expert < 0) return;
+    const int n0 = tl.nt * BNF;
+    const int rows = g.row_end - g.row_begin;  // >= 1; may exceed BM
+
+    // ---- copy roles: one copy instruction fills 8 tile rows (1024 bytes); lane l lands on
+    //      row l/8, chunk position l%8 and therefore fetches chunk (l%8) ^ key(row) ----
+    const int lrow = lane >> 3, lpos = lane & 7;
+    int chunkc[2];  // for even / odd 8-row groups (the key depends on row bits 0..3)
+#pragma unroll
+    for (int par = 0; par < 2; ++par) chunkc[par] = lpos ^ swz_key(par * 8 + lrow);
+    const unsigned char *baseA = reinterpret_cast<const unsigned char *>(A + (size_t)g.row_begin * lda);
+    const unsigned char *baseB0 = reinterpret_cast<const unsigned char *>(B0 + (size_t)g.expert * N * Kdim);
+    const unsigned char *baseB1 =
+        MODE == 0 ? reinterpret_cast<const unsigned char *>(B1 + (size_t)g.expert * N * Kdim) : baseB0;
+    uint32_t offA[GA], offB[GB], rowB[GB];
+#pragma unroll
+    for (int i = 0; i < GA; ++i) {
+        const int rg = wave * GA + i;
+        int r = rg * 8 + lrow;
+        r = r < rows ? r : rows - 1;
+        offA[i] = (uint32_t)r * (uint32_t)lda * 2u + (uint32_t)chunkc[rg & 1] * 16u;
+    }
+#pragma unroll
+    for (int i = 0; i < GB; ++i) {
+        const int rg = wave * GB + i;
+        int r = rg * 8 + lrow;
+        if (MODE == 0 && r >= BN / 2) r -= BN / 2;
+        int c = n0 + r;
+        c = c < N ? c : N - 1;
+        rowB[i] = (uint32_t)c * (uint32_t)Kdim * 2u;
+        offB[i] = rowB[i] + (uint32_t)chunkc[rg & 1] * 16u;
+    }
+    // GB*8 rows per wave divide BN/2, so a wave's B rows are all gate rows or all up rows
+    const unsigned char *baseB = (MODE == 0 && wave * GB * 8 >= BN / 2) ? baseB1 : baseB0;
+
+    const int nk = (Kdim + BK - 1) / BK;
+    const bool ktail = (Kdim % BK) != 0;
+    auto copy_slice = [&](int kt, unsigned char *stage) {
+        const uint32_t kb = (uint32_t)kt * ROWB;
+        const bool last = ktail && kt == nk - 1;
+#pragma unroll
+        for (int i = 0; i < GA; ++i) copy16_to_lds(baseA + offA[i] + kb, stage + (wave * GA + i) * 1024);
+#pragma unroll
+        for (int i = 0; i < GB; ++i) {  // a B chunk past K is taken from chunk 0: it meets A's zero padding
+            const int rg = wave * GB + i;
+            const bool clampB = last && kt * BK + chunkc[rg & 1] * 8 >= Kdim;
+            copy16_to_lds(baseB + (clampB ? rowB[i] : offB[i] + kb), stage + A_BYTES + rg * 1024);
+        }
+    };
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+
+    const int fr = lane & 31, fh = lane >> 5;
+    uint32_t rdA[FM], rdB[FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) rdA[i] = (uint32_t)(wm * TM + i * 32 + fr) * ROWB;
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        int r;
+        if (MODE == 0)
+            r = (j < FN / 2) ? wn * (TN / 2) + j * 32 : BN / 2 + wn * (TN / 2) + (j - FN / 2) * 32;
+        else
+            r = wn * TN + j * 32;
+        rdB[j] = (uint32_t)A_BYTES + (uint32_t)(r + fr) * ROWB;
+    }
+    const int sw = swz_key(fr);
+    // waves whose whole M range lies past the group's end only help with the copies
+    const bool active = __builtin_amdgcn_readfirstlane(rows - wm * TM) > 0;
+
+    bf16x8 af[2][FM], bfr[2][FN];
+    auto read_frags = [&](const unsigned char *stage, int kk, int set) {
+        const uint32_t ch = (uint32_t)(((kk * 2 + fh) ^ sw) * 16);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) af[set][i] = *reinterpret_cast<const bf16x8 *>(stage + rdA[i] + ch);
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bfr[set][j] = *reinterpret_cast<const bf16x8 *>(stage + rdB[j] + ch);
+    };
+    auto mfma_set = [&](int set) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)  // operands swapped: the lane's 4-element runs lie along n
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i], acc[i][j], 0, 0, 0);
+    };
+    // One 64-wide slice: start the copy of the next slice into the other stage, multiply
+    // this one (fragments of k-step kk+1 are read while the MFMAs of kk issue), then hand
+    // the other stage over.
+    auto slice_step = [&](int kt, const unsigned char *cur, unsigned char *nxt) {
+        if (kt + 1 < nk) copy_slice(kt + 1, nxt);
+        if (active) {
+            read_frags(cur, 0, 0);
+#pragma unroll
+            for (int kk = 0; kk < NKK; ++kk) {
+                if (kk + 1 < NKK) read_frags(cur, kk + 1, (kk + 1) & 1);
+                __builtin_amdgcn_sched_barrier(0);
+                mfma_set(kk & 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        wait_copies_but<0>();
+        lds_barrier();
+    };
+
+    copy_slice(0, st0);
+    wait_copies_but<0>();
+    lds_barrier();
+    for (int kt = 0; kt < nk; kt += 2) {
+        slice_step(kt, st0, st1);
+        if (kt + 1 >= nk) break;
+        slice_step(kt + 1, st1, st0);
+    }
+
+    // ---- epilogue.  Fragment (i, j) holds C^T: lane (fr, fh), register v is
+    //      row m = i*32 + fr, column n = j*32 + 8*(v/4) + 4*fh + v%4  -> 8-byte stores ----
+    uint16_t *outb = out + (size_t)g.row_begin * ldo;
+    constexpr int FJ = MODE == 0 ? FN / 2 : FN;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int r = wm * TM + i * 32 + fr;
+        if (r >= rows) continue;
+#pragma unroll
+        for (int j = 0; j < FJ; ++j) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int col = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN) + j * 32 + q * 8 + fh * 4;
+                uint2 pk = make_uint2(0, 0);
+                if (col >= N) {
+                    // pass 0 keeps the padding columns of h at zero for pass 1's k tail
+                    if (col < zero_to) *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
+                    continue;
+                }
+                float v4[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (MODE == 0)
+                        v4[u] = silu_mul(acc[i][j][q * 4 + u], acc[i][j + FN / 2][q * 4 + u]);
+                    else
+                        v4[u] = acc[i][j][q * 4 + u];
+                }
+                pk.x = pack_bf16x2(v4[0], v4[1]);
+                pk.y = pack_bf16x2(v4[2], v4[3]);
+                *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
+            }
+        }
+    }
+}
+
+// pass 0: a = x_perm [A_cap, d] (d % 64 == 0), out = h with row pitch ldh >= F, columns
+//         [F, ldh) zeroed;   pass 1: a = h (pitch ldh, zero padded to 64), out = y_perm.
+int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t *offsets, int E_local,
+                             int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1,
+                             uint16_t *out, int ldo, hipStream_t st) {
+    constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
+    const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
+    const int ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
+    const int64_t grid = (mtiles * ntn + 7) / 8 * 8;
+    if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
+    if (pass == 0)
+        ffn_bf16_dma_kernel<0, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(
+            a, lda, offsets, E_local, (int)A_cap, F, d, b0, b1, out, ldo, ntn, ldo);
+    else
+        ffn_bf16_dma_kernel<1, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(
+            a, lda, offsets, E_local, (int)A_cap, d, F, b0, nullptr, out, ldo, ntn, 0);
+    return launch_status();
+}
+
+}  // namespace c2r

@@ -7,8 +7,10 @@
 //    The W_g row for the current k is wave-uniform, so it is fetched with scalar
 //    loads and used as the SGPR operand of v_fma_f32.  The accumulation order
 //    inside a chunk is exactly the ABI's declared order (one fma per k,
-//    ascending).  Chunk results go to scratch as part[chunk][expert][token]
-//    (token fastest: coalesced both here and in the reader).
+//    ascending).  Chunk results go to scratch as part[tile][chunk][expert][64]
+//    (token fastest: coalesced both here and in the reader, and one tile's
+//    partials are one contiguous run).  When there are few token tiles the
+//    experts are also split over several waves so that every SIMD has work.
 //  route_select_kernel: lane = token.  Adds the chunk results left to right,
 //    adds the bias, then does arg max / masked top-(K-1) entirely in registers
 //    with one 64-bit collaborator mask per expert held in LDS.
@@ -25,11 +27,11 @@ __global__ __launch_bounds__(256) void pad_router_kernel(const float *__restrict
     Wp[i] = e < E ? Wg[(int64_t)k * E + e] : 0.0f;
 }
 
-template <bool BF16, int EP>
+template <bool BF16, int EP>  // EP: experts handled by one wave
 __global__ __launch_bounds__(64) void route_partial_kernel(const void *__restrict__ x,
                                                            const float *__restrict__ W, int ldw,
-                                                           int64_t T, int d, int nchunk,
-                                                           int64_t Tpad, float *__restrict__ part) {
+                                                           int64_t T, int d, int nchunk, int esplit,
+                                                           int ep_total, float *__restrict__ part) {
     constexpr int VEC = BF16 ? 8 : 4;  // elements per 16-byte vector
     constexpr int KSUB = 8 * VEC;      // elements per staged row segment (128 bytes)
     constexpr int PITCH = 128 + 16;    // LDS row pitch in bytes: odd multiple of 16 -> no conflicts
@@ -37,8 +39,10 @@ __global__ __launch_bounds__(64) void route_partial_kernel(const void *__restric
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][64 * PITCH];
 
     const int lane = threadIdx.x;
-    const int chunk = (int)(blockIdx.x % nchunk);
-    const int64_t tile = blockIdx.x / nchunk;
+    const int split = (int)(blockIdx.x % esplit);
+    const int chunk = (int)((blockIdx.x / esplit) % nchunk);
+    const int64_t tile = blockIdx.x / ((int64_t)esplit * nchunk);
+    W += split * EP;
     const int k_begin = chunk * C2R_CANON_CHUNK;
     const int k_end = min(d, k_begin + C2R_CANON_CHUNK);
     const int64_t t0 = tile * 64;
@@ -105,8 +109,9 @@ __global__ __launch_bounds__(64) void route_partial_kernel(const void *__restric
         __syncthreads();
         buf ^= 1;
     }
+    float *dst = part + (((size_t)tile * nchunk + chunk) * ep_total + split * EP) * 64 + lane;
 #pragma unroll
-    for (int e = 0; e < EP; ++e) part[((size_t)chunk * EP + e) * Tpad + t0 + lane] = acc[e];
+    for (int e = 0; e < EP; ++e) dst[e * 64] = acc[e];
 }
 
 // Among experts whose bit is set in m: the largest logit, first one standing
@@ -126,13 +131,13 @@ __device__ __forceinline__ void pick(const float (&l)[EP], uint64_t m, int &bi, 
 }
 
 template <int EP, bool ROWMAJOR>
-__global__ __launch_bounds__(256) void route_select_kernel(
-    const float *__restrict__ src, int nchunk, int64_t Tpad, const float *__restrict__ bias,
+__global__ __launch_bounds__(64) void route_select_kernel(
+    const float *__restrict__ src, int nchunk, const float *__restrict__ bias,
     int64_t T, int E, int K, const int32_t *__restrict__ collab_idx, int Tc,
     int32_t *__restrict__ topk_idx, float *__restrict__ gates, float *__restrict__ logits_out) {
     __shared__ uint64_t mask_tab[C2R_MAX_E];
     constexpr int LP = EP + 1;  // odd pitch: per-lane row reads hit distinct banks
-    __shared__ float tile[ROWMAJOR ? 4 * 64 * LP : 1];
+    __shared__ float tile[ROWMAJOR ? 64 * LP : 1];
 
     const uint64_t all = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
     if (threadIdx.x < C2R_MAX_E) {
@@ -151,13 +156,13 @@ __global__ __launch_bounds__(256) void route_select_kernel(
         mask_tab[e] = m;
     }
 
-    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t t = (int64_t)blockIdx.x * 64 + threadIdx.x;
+    const int lane = threadIdx.x;
     float l[EP];
     if constexpr (ROWMAJOR) {
         // wave-private transpose: 64 consecutive rows of E floats are one contiguous run
-        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-        float *tl = tile + wave * 64 * LP;
-        const int64_t tw = (int64_t)blockIdx.x * 256 + wave * 64;
+        float *tl = tile;
+        const int64_t tw = (int64_t)blockIdx.x * 64;
         const int64_t rows = T - tw < 64 ? T - tw : 64;  // may be <= 0
         const int64_t nflt = rows > 0 ? rows * E : 0;
         const float *base = src + tw * E;
@@ -184,12 +189,13 @@ __global__ __launch_bounds__(256) void route_select_kernel(
 #pragma unroll
         for (int e = 0; e < EP; ++e) l[e] = (e < E && lane < rows) ? tl[lane * LP + e] : 0.0f;
     } else {
-        const int64_t tt = t < Tpad ? t : Tpad - 1;
+        const float *p = src + (size_t)blockIdx.x * nchunk * EP * 64 + lane;
 #pragma unroll
-        for (int e = 0; e < EP; ++e) l[e] = src[(size_t)e * Tpad + tt];
+        for (int e = 0; e < EP; ++e) l[e] = p[e * 64];
         for (int c = 1; c < nchunk; ++c) {
+            p += EP * 64;
 #pragma unroll
-            for (int e = 0; e < EP; ++e) l[e] = l[e] + src[((size_t)c * EP + e) * Tpad + tt];
+            for (int e = 0; e < EP; ++e) l[e] = l[e] + p[e * 64];
         }
         if (bias) {
 #pragma unroll
@@ -240,7 +246,7 @@ static int check_route_args(int64_t T, int E, int K, const int32_t *collab_idx, 
 static inline int ep_of(int E) { return (E + 3) / 4 * 4; }
 
 struct RouteLayout {
-    int EP, nchunk;
+    int EP, nchunk, esplit;
     int64_t Tpad;
     size_t part_bytes, wpad_bytes;
 };
@@ -251,6 +257,16 @@ static RouteLayout route_layout(int64_t T, int d, int E) {
     L.nchunk = (d + C2R_CANON_CHUNK - 1) / C2R_CANON_CHUNK;
     if (L.nchunk < 1) L.nchunk = 1;
     L.Tpad = (T + 63) / 64 * 64;
+    // split the experts over `esplit` waves (each a multiple of 4 experts, at least 8) until
+    // there are about two waves per SIMD (256 CUs x 4 SIMDs)
+    L.esplit = 1;
+    const int64_t base_waves = L.Tpad / 64 * L.nchunk;
+    for (int s = 1; s <= L.EP / 4; ++s) {
+        if ((L.EP / 4) % s != 0) continue;
+        if (L.EP / s < 8 && s > 1) break;
+        L.esplit = s;
+        if (base_waves * s >= 2048) break;
+    }
     L.part_bytes = round_up((size_t)L.nchunk * L.EP * (size_t)L.Tpad * sizeof(float), 256);
     L.wpad_bytes = (E % 4) ? round_up((size_t)d * L.EP * sizeof(float), 256) : 0;
     return L;
@@ -314,18 +330,18 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
         ldw = L.EP;
     }
     const int64_t ntiles = L.Tpad / 64;
-    const int64_t nblk = ntiles * L.nchunk;
+    const int64_t nblk = ntiles * L.nchunk * L.esplit;
+    const int EPW = L.EP / L.esplit;
     if (nblk >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (x_dt == C2R_BF16) {
-        C2R_EP_SWITCH(L.EP, route_partial_kernel<true, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
-                                x, W, ldw, T, d, L.nchunk, L.Tpad, part));
+        C2R_EP_SWITCH(EPW, route_partial_kernel<true, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
+                               x, W, ldw, T, d, L.nchunk, L.esplit, L.EP, part));
     } else {
-        C2R_EP_SWITCH(L.EP, route_partial_kernel<false, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
-                                x, W, ldw, T, d, L.nchunk, L.Tpad, part));
+        C2R_EP_SWITCH(EPW, route_partial_kernel<false, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
+                               x, W, ldw, T, d, L.nchunk, L.esplit, L.EP, part));
     }
-    const unsigned nsel = (unsigned)((T + 255) / 256);
-    C2R_EP_SWITCH(L.EP, route_select_kernel<EP, false><<<dim3(nsel), dim3(256), 0, st>>>(
-                            part, L.nchunk, L.Tpad, bias, T, E, K, collab_idx, Tc, topk_idx, gates, logits_out));
+    C2R_EP_SWITCH(L.EP, route_select_kernel<EP, false><<<dim3((unsigned)ntiles), dim3(64), 0, st>>>(
+                            part, L.nchunk, bias, T, E, K, collab_idx, Tc, topk_idx, gates, logits_out));
     return launch_status();
 }
 
@@ -338,10 +354,11 @@ extern "C" int c2r_route_from_logits(const float *logits, int64_t T, int E, int 
     if (!logits || !topk_idx || !gates) return C2R_ERR_INVALID_ARG;
     if (!aligned(logits, 16)) return C2R_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const unsigned nsel = (unsigned)((T + 255) / 256);
+    const int64_t nsel = (T + 63) / 64;
+    if (nsel >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     const int EPV = ep_of(E);
-    C2R_EP_SWITCH(EPV, route_select_kernel<EP, true><<<dim3(nsel), dim3(256), 0, st>>>(
-                           logits, 1, (int64_t)0, (const float *)nullptr, T, E, K, collab_idx, Tc, topk_idx, gates,
+    C2R_EP_SWITCH(EPV, route_select_kernel<EP, true><<<dim3((unsigned)nsel), dim3(64), 0, st>>>(
+                           logits, 1, (const float *)nullptr, T, E, K, collab_idx, Tc, topk_idx, gates,
                            (float *)nullptr));
     return launch_status();
 }

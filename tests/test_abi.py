@@ -36,6 +36,8 @@ def test_workspace_query_is_host_only():
     assert c2r.workspace_bytes(c2r.STAGE_ROUTE, 8192, 2048, 60, 4, 0, c2r.BF16) == 8 * 60 * 8192 * 4
     assert c2r.workspace_bytes(c2r.STAGE_ROUTE, 100, 256, 8, 2, 0, c2r.F32) == 1 * 8 * 128 * 4
     assert c2r.workspace_bytes(c2r.STAGE_EXPERT_FFN, 32768, 2048, 60, 1, 1408, c2r.BF16) == 32768 * 1408 * 2
+    assert c2r.workspace_bytes(c2r.STAGE_EXPERT_FFN, 100, 4096, 16, 1, 688, c2r.BF16) == 100 * 704 * 2 + 0 * 256
+    assert c2r.workspace_bytes(c2r.STAGE_EXPERT_FFN, 64, 256, 8, 1, 520, c2r.F32) == 64 * 520 * 4
     assert c2r.workspace_bytes(c2r.STAGE_PERMUTE, 8192, 2048, 60, 4, 0, c2r.BF16) > 0
 
 
