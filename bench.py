@@ -28,6 +28,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="C3", help="C1|C2|C3|C5 (C3 = Qwen1.5-MoE-A2.7B-shaped layer)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain device-to-device copies of known size (to scale rocprofv3's "
+                         "FETCH_SIZE / WRITE_SIZE counters) and exit")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1",
@@ -41,6 +44,16 @@ def main():
     c2r.lib()  # fails loudly if the HIP library is not built
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        nbytes = 512 << 20
+        src = torch.full((nbytes // 4,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(10):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "bytes_read_per_copy": nbytes, "bytes_written_per_copy": nbytes,
+                          "copies": 10}))
+        return
     w = wl.WORKLOADS[args.workload]
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     sz = 2 if w.dtype == "bf16" else 4
@@ -141,14 +154,21 @@ def main():
     ffn_tf = (fl_gu + fl_dn + fl_sgu + fl_sdn) / ffn_ms / 1e9
     stage_info["expert_ffn_all"] = {"ms": ffn_ms, "TFLOPs": ffn_tf, "frac_mfma": ffn_tf / PEAK["mfma_bf16_TFLOPs"]}
 
+    # HBM traffic of the dominant kernel per launch, from the committed rocprofv3 --pmc summary (if any)
+    traffic = None
+    tfile = os.path.join(ROOT, "profiles", f"ffn_gate_up_{w.name}_hbm_traffic.txt")
+    if os.path.exists(tfile):
+        for line in open(tfile):
+            if line.startswith("traffic_bytes_per_launch:"):
+                traffic = float(line.split(":")[1])
     # dominant kernel: the gate/up pass (launched for the routed groups and, if any, the shared expert)
     n_launch = 2 if shared else 1
     dom_ms = (st_ms["ffn_gate_up"] + st_ms["shared_gate_up"]) / n_launch
     dom_fl = (fl_gu + fl_sgu) / n_launch
     if w.dtype == "bf16":
-        roofline = {"kernel": "ffn_bf16_kernel<0> (gate/up + SwiGLU)", "bound": "mfma",
+        roofline = {"kernel": "ffn_bf16_dma_kernel<0> (gate/up + SwiGLU)", "bound": "mfma",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["mfma_bf16_TFLOPs"], "unit": "TFLOP/s",
-                    "frac": dom_fl / dom_ms / 1e9 / PEAK["mfma_bf16_TFLOPs"], "traffic": None,
+                    "frac": dom_fl / dom_ms / 1e9 / PEAK["mfma_bf16_TFLOPs"], "traffic": traffic,
                     "avg_launch_ms": dom_ms, "launches_per_step": n_launch}
     else:
         roofline = {"kernel": "ffn_f32_kernel<0> (gate/up + SwiGLU)", "bound": "alu",

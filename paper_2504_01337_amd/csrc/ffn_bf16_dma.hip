@@ -82,10 +82,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    GroupTile g = find_group_tile<BM>(offsets, E_local, A_cap, -1);
-    const TileId tl = xcd_grouped_tile(g.total_mtiles, ntn);
+    const GroupMap gmap = build_group_map<BM>(offsets, E_local, A_cap);
+    const TileId tl = xcd_grouped_tile(gmap.total_mtiles, ntn);
     if (!tl.valid) return;
-    g = find_group_tile<BM>(offsets, E_local, A_cap, tl.mt);
+    const GroupTile g = locate_group_tile(gmap, tl.mt, BM);
     if (g.expert < 0) return;
     const int n0 = tl.nt * BNF;
     const int rows = g.row_end - g.row_begin;  // >= 1; may exceed BM
@@ -247,7 +247,7 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
     const int ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
-    const int64_t grid = (mtiles * ntn + 7) / 8 * 8;
+    const int64_t grid = xcd_grouped_grid(mtiles, ntn);
     if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (pass == 0)
         ffn_bf16_dma_kernel<0, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(

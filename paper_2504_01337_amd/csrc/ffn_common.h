@@ -5,47 +5,62 @@
 namespace c2r {
 
 struct GroupTile {
-    int expert;       // local expert slot, -1: this workgroup has no tile
-    int row_begin;    // first row of the tile in x_perm
-    int row_end;      // one past the expert's last row
-    int total_mtiles; // M-tiles over all experts
+    int expert;        // local expert slot, -1: no such tile
+    int row_begin;     // first row of the tile in x_perm
+    int row_end;       // one past the expert's last row
 };
 
-// Every wave calls this with all 64 lanes active.  Lane e sizes expert e's row
-// range (offsets are clamped to [0, A_cap] so a corrupt array cannot send a load
-// out of bounds), a wave scan turns tile counts into tile ranges, and the M-tile
-// number mt is located with a ballot.  E_local <= 64.
+// Per-wave map from M-tile number to expert group, held one expert per lane.  M-tiles are
+// numbered expert after expert in slot order (measured: numbering the big experts first, or
+// dealing tile groups round-robin to the XCDs, costs more in lost L2 locality than the
+// better balance returns).
+struct GroupMap {
+    int lo, hi;        // this lane's expert: row range (clamped to [0, A_cap])
+    int tiles;         // its number of M-tiles
+    int first;         // its first M-tile number
+    int total_mtiles;  // M-tiles over all experts
+};
+
+// Every wave calls this with all 64 lanes active; E_local <= 64.  Offsets are clamped so
+// that a corrupt array cannot send a load out of bounds.
 template <int BM>
-__device__ __forceinline__ GroupTile find_group_tile(const int32_t *__restrict__ offsets, int E_local,
-                                                      int A_cap, int mt) {
+__device__ __forceinline__ GroupMap build_group_map(const int32_t *__restrict__ offsets, int E_local,
+                                                     int A_cap) {
     const int lane = lane_id();
-    int lo = 0, hi = 0;
+    GroupMap m;
+    m.lo = m.hi = 0;
     if (lane < E_local) {
-        lo = offsets[lane];
-        hi = offsets[lane + 1];
+        int lo = offsets[lane], hi = offsets[lane + 1];
         lo = lo < 0 ? 0 : (lo > A_cap ? A_cap : lo);
         hi = hi < lo ? lo : (hi > A_cap ? A_cap : hi);
+        m.lo = lo;
+        m.hi = hi;
     }
-    const int tiles = (hi - lo + BM - 1) / BM;
-    int incl = tiles;
+    const int cnt = m.hi - m.lo;
+    m.tiles = (cnt + BM - 1) / BM;
+    int incl = m.tiles;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         const int v = __shfl_up(incl, off);
         if (lane >= off) incl += v;
     }
+    m.first = incl - m.tiles;
+    m.total_mtiles = __shfl(incl, 63);
+    return m;
+}
+
+__device__ __forceinline__ GroupTile locate_group_tile(const GroupMap &m, int mt, int BM) {
     GroupTile g;
-    g.total_mtiles = __shfl(incl, 63);
-    const uint64_t hit = __ballot(incl > mt);
-    if (mt < 0 || hit == 0) {
+    const uint64_t hit = __ballot(mt >= m.first && mt < m.first + m.tiles);
+    if (hit == 0) {
         g.expert = -1;
         g.row_begin = g.row_end = 0;
         return g;
     }
     const int e = __ffsll((unsigned long long)hit) - 1;
-    const int excl_e = __shfl(incl - tiles, e);
     g.expert = e;
-    g.row_begin = __shfl(lo, e) + (mt - excl_e) * BM;
-    g.row_end = __shfl(hi, e);
+    g.row_begin = __shfl(m.lo, e) + (mt - __shfl(m.first, e)) * BM;
+    g.row_end = __shfl(m.hi, e);
     return g;
 }
 
@@ -64,18 +79,19 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ int swz_key(int row) { return ((row >> 1) & 7) ^ ((row & 1) << 2); }
 
 struct TileId {
-    int mt, nt, total_mtiles;
+    int mt, nt;
     bool valid;
 };
 
 // Workgroup -> tile.  Tiles are numbered so that consecutive numbers walk GM M-tiles
 // (fastest) by all N-tiles: the ~32 workgroups running together on one XCD then cover a
 // near-square block of tiles and re-use each other's A and B k-slices out of that XCD's
-// L2.  Each XCD (workgroup id mod 8) gets one contiguous range of tile numbers.
+// L2.  Each XCD (workgroup id mod 8) gets one contiguous range of tile numbers, so an
+// expert's weights are mostly streamed by one XCD.
+constexpr int TILE_GM = 4;
+
 __device__ __forceinline__ TileId xcd_grouped_tile(int total_mtiles, int ntn) {
-    constexpr int GM = 4;
     TileId t;
-    t.total_mtiles = total_mtiles;
     t.valid = false;
     t.mt = t.nt = 0;
     const int total = total_mtiles * ntn;
@@ -83,14 +99,19 @@ __device__ __forceinline__ TileId xcd_grouped_tile(int total_mtiles, int ntn) {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int tile = xcd * per_xcd + slot;
     if (slot >= per_xcd || tile >= total) return t;
-    const int grp = tile / (GM * ntn);
-    const int first_m = grp * GM;
-    const int gsz = total_mtiles - first_m < GM ? total_mtiles - first_m : GM;
-    const int rem = tile - grp * GM * ntn;
+    const int grp = tile / (TILE_GM * ntn);
+    const int first_m = grp * TILE_GM;
+    const int gsz = total_mtiles - first_m < TILE_GM ? total_mtiles - first_m : TILE_GM;
+    const int rem = tile - grp * TILE_GM * ntn;
     t.mt = first_m + rem % gsz;
     t.nt = rem / gsz;
     t.valid = true;
     return t;
+}
+
+// Host side: workgroups to launch (a multiple of 8 that covers every tile).
+static inline int64_t xcd_grouped_grid(int64_t mtiles_bound, int ntn) {
+    return (mtiles_bound * ntn + 7) / 8 * 8;
 }
 
 }  // namespace c2r

@@ -19,7 +19,8 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float *__restrict__ 
     __shared__ float Bs[MODE == 0 ? 2 : 1][F32_BK][F32_BN + 4];
     const int ntn = (N + F32_BN - 1) / F32_BN;
     const int mt = blockIdx.x / ntn, nt = blockIdx.x % ntn;
-    const GroupTile g = find_group_tile<F32_BM>(offsets, E_local, A_cap, mt);
+    const GroupMap gmap = build_group_map<F32_BM>(offsets, E_local, A_cap);
+    const GroupTile g = locate_group_tile(gmap, mt, F32_BM);
     if (g.expert < 0) return;
     const int n0 = nt * F32_BN;
     const float *Bg = B0 + (size_t)g.expert * N * Kdim;

@@ -18,20 +18,25 @@
 
 namespace c2r {
 
-template <int EP>
-__global__ __launch_bounds__(256) void pad_router_kernel(const float *__restrict__ Wg, int d, int E,
-                                                         float *__restrict__ Wp) {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (int64_t)d * EP) return;
-    int k = (int)(i / EP), e = (int)(i % EP);
+// Wp[s][k][j] = W_g[k][s*epw + j] (zero past E): each expert split gets its own dense
+// [d, epw] matrix, so a wave streams its W rows as one contiguous run of scalar loads.
+__global__ __launch_bounds__(256) void pack_router_kernel(const float *__restrict__ Wg, int d, int E,
+                                                          int epw, int esplit, float *__restrict__ Wp) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= (int64_t)d * epw * esplit) return;
+    const int j = (int)(i % epw);
+    const int k = (int)((i / epw) % d);
+    const int s = (int)(i / ((int64_t)epw * d));
+    const int e = s * epw + j;
     Wp[i] = e < E ? Wg[(int64_t)k * E + e] : 0.0f;
 }
 
 template <bool BF16, int EP>  // EP: experts handled by one wave
 __global__ __launch_bounds__(64) void route_partial_kernel(const void *__restrict__ x,
-                                                           const float *__restrict__ W, int ldw,
+                                                           const float *__restrict__ W,
                                                            int64_t T, int d, int nchunk, int esplit,
-                                                           int ep_total, float *__restrict__ part) {
+                                                           int ep_total, int64_t ntiles,
+                                                           float *__restrict__ part) {
     constexpr int VEC = BF16 ? 8 : 4;  // elements per 16-byte vector
     constexpr int KSUB = 8 * VEC;      // elements per staged row segment (128 bytes)
     constexpr int PITCH = 128 + 16;    // LDS row pitch in bytes: odd multiple of 16 -> no conflicts
@@ -39,10 +44,12 @@ __global__ __launch_bounds__(64) void route_partial_kernel(const void *__restric
     __shared__ __attribute__((aligned(16))) unsigned char lds[2][64 * PITCH];
 
     const int lane = threadIdx.x;
-    const int split = (int)(blockIdx.x % esplit);
-    const int chunk = (int)((blockIdx.x / esplit) % nchunk);
-    const int64_t tile = blockIdx.x / ((int64_t)esplit * nchunk);
-    W += split * EP;
+    // token tile fastest: the workgroups dispatched together share one (chunk, split), i.e. the
+    // same W rows, which then stay hot in the scalar cache and L2
+    const int64_t tile = blockIdx.x % ntiles;
+    const int cs = (int)(blockIdx.x / ntiles);
+    const int split = cs % esplit, chunk = cs / esplit;
+    W += (size_t)split * d * EP;  // this split's dense [d, EP] matrix
     const int k_begin = chunk * C2R_CANON_CHUNK;
     const int k_end = min(d, k_begin + C2R_CANON_CHUNK);
     const int64_t t0 = tile * 64;
@@ -100,7 +107,7 @@ __global__ __launch_bounds__(64) void route_partial_kernel(const void *__restric
             }
 #pragma unroll
             for (int j = 0; j < VEC; ++j) {
-                const float *__restrict__ wrow = W + (size_t)(k0 + v * VEC + j) * ldw;
+                const float *__restrict__ wrow = W + (size_t)(k0 + v * VEC + j) * EP;
 #pragma unroll
                 for (int e = 0; e < EP; ++e) acc[e] = __builtin_fmaf(xv[j], wrow[e], acc[e]);
             }
@@ -268,7 +275,7 @@ static RouteLayout route_layout(int64_t T, int d, int E) {
         if (base_waves * s >= 2048) break;
     }
     L.part_bytes = round_up((size_t)L.nchunk * L.EP * (size_t)L.Tpad * sizeof(float), 256);
-    L.wpad_bytes = (E % 4) ? round_up((size_t)d * L.EP * sizeof(float), 256) : 0;
+    L.wpad_bytes = (E % 4 || L.esplit > 1) ? round_up((size_t)d * L.EP * sizeof(float), 256) : 0;
     return L;
 }
 
@@ -321,24 +328,22 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(ws);
     const float *W = Wg;
-    int ldw = E;
+    const int EPW = L.EP / L.esplit;
     if (L.wpad_bytes) {
         float *Wp = reinterpret_cast<float *>(static_cast<char *>(ws) + L.part_bytes);
         const int64_t n = (int64_t)d * L.EP;
-        C2R_EP_SWITCH(L.EP, pad_router_kernel<EP><<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(Wg, d, E, Wp));
+        pack_router_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(Wg, d, E, EPW, L.esplit, Wp);
         W = Wp;
-        ldw = L.EP;
     }
     const int64_t ntiles = L.Tpad / 64;
     const int64_t nblk = ntiles * L.nchunk * L.esplit;
-    const int EPW = L.EP / L.esplit;
     if (nblk >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (x_dt == C2R_BF16) {
         C2R_EP_SWITCH(EPW, route_partial_kernel<true, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
-                               x, W, ldw, T, d, L.nchunk, L.esplit, L.EP, part));
+                               x, W, T, d, L.nchunk, L.esplit, L.EP, ntiles, part));
     } else {
         C2R_EP_SWITCH(EPW, route_partial_kernel<false, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
-                               x, W, ldw, T, d, L.nchunk, L.esplit, L.EP, part));
+                               x, W, T, d, L.nchunk, L.esplit, L.EP, ntiles, part));
     }
     C2R_EP_SWITCH(L.EP, route_select_kernel<EP, false><<<dim3((unsigned)ntiles), dim3(64), 0, st>>>(
                             part, L.nchunk, bias, T, E, K, collab_idx, Tc, topk_idx, gates, logits_out));
