@@ -9,8 +9,9 @@
 // one slice buys nothing).  Lane l lands at byte 16*l of the 1 KB run, i.e. row l/8, chunk
 // position l%8, so the lane fetches the global chunk (l%8) ^ swz_key(row) and the
 // swizzled layout falls out without any LDS write instruction.  The copy of slice k+1
-// is asynchronous and overlaps the MFMAs of slice k; one "my copies landed" wait + bare
-// barrier per slice hands the stage over.
+// is asynchronous and overlaps the MFMAs of slice k; one "my copies landed, my reads
+// returned" wait + bare barrier per slice, placed before the slice's last k-step, hands
+// both stages over (see slice_step).
 //
 // Contract (checked by the launcher): the contraction length seen by A is padded to a
 // multiple of 64 with zeros (lda >= 64 * ceil(K/64)); a B chunk past K is re-read from
@@ -44,6 +45,13 @@ template <int N>
 __device__ __forceinline__ void wait_copies_but() {
 #if defined(__HIP_DEVICE_COMPILE__)
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+#endif
+}
+
+// vmcnt(0) and lgkmcnt(0): this wave's copies have landed and its LDS reads have returned.
+__device__ __forceinline__ void wait_copies_and_lds() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0x0070);
 #endif
 }
 
@@ -123,18 +131,22 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 
     const int nk = (Kdim + BK - 1) / BK;
     const bool ktail = (Kdim % BK) != 0;
-    auto copy_slice = [&](int kt, unsigned char *stage) {
+    // Piece p of a slice's copy: p < GA are this wave's A row groups, the rest its B groups.
+    // Copies are issued one at a time between MFMAs (see slice_step): the texture-address
+    // unit takes one 64-lane x 16-byte request per ~16 cycles, so a burst of all of a
+    // workgroup's copies would hold every wave at its copy instructions for ~1000 cycles
+    // with the matrix pipe idle.
+    auto copy_piece = [&](int kt, unsigned char *stage, int p) {
         const uint32_t kb = (uint32_t)kt * ROWB;
-        const bool last = ktail && kt == nk - 1;
-#pragma unroll
-        for (int i = 0; i < GA; ++i) copy16_to_lds(baseA + offA[i] + kb, stage + (wave * GA + i) * 1024);
-#pragma unroll
-        for (int i = 0; i < GB; ++i) {  // a B chunk past K is taken from chunk 0: it meets A's zero padding
-            const int rg = wave * GB + i;
-            const bool clampB = last && kt * BK + chunkc[rg & 1] * 8 >= Kdim;
+        if (p < GA) {
+            copy16_to_lds(baseA + offA[p] + kb, stage + (wave * GA + p) * 1024);
+        } else {  // a B chunk past K is taken from chunk 0: it meets A's zero padding
+            const int i = p - GA, rg = wave * GB + i;
+            const bool clampB = ktail && kt == nk - 1 && kt * BK + chunkc[rg & 1] * 8 >= Kdim;
             copy16_to_lds(baseB + (clampB ? rowB[i] : offB[i] + kb), stage + A_BYTES + rg * 1024);
         }
     };
+    constexpr int NPIECE = GA + GB;
 
     f32x16 acc[FM][FN];
 #pragma unroll
@@ -169,40 +181,108 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #pragma unroll
         for (int j = 0; j < FN; ++j) bfr[set][j] = *reinterpret_cast<const bf16x8 *>(stage + rdB[j] + ch);
     };
-    auto mfma_set = [&](int set) {
-#pragma unroll
-        for (int i = 0; i < FM; ++i)
-#pragma unroll
-            for (int j = 0; j < FN; ++j)  // operands swapped: the lane's 4-element runs lie along n
-                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[set][j], af[set][i], acc[i][j], 0, 0, 0);
-    };
-    // One 64-wide slice: start the copy of the next slice into the other stage, multiply
-    // this one (fragments of k-step kk+1 are read while the MFMAs of kk issue), then hand
-    // the other stage over.
-    auto slice_step = [&](int kt, const unsigned char *cur, unsigned char *nxt) {
-        if (kt + 1 < nk) copy_slice(kt + 1, nxt);
+    static_assert(NPIECE == 8 && FM == 4 && FN == 2, "copy schedule below: 3 + 3 + 2 pieces over three k-steps");
+    // MFMAs of one k-step (operands swapped: the lane's 4-element runs lie along n) with up
+    // to three copy pieces P0.. of slice CKT slipped in after every second MFMA.  Macros, so
+    // that every fragment and piece index is a literal and the arrays stay in registers.
+#define C2R_MFMA(SET, I, J) \
+    acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[SET][J], af[SET][I], acc[I][J], 0, 0, 0)
+#define C2R_COPY_IF(Q, NCP, CKT, CST, P0)           \
+    if ((Q) < (NCP)) {                              \
+        __builtin_amdgcn_sched_barrier(0);          \
+        copy_piece(CKT, CST, (P0) + (Q));           \
+        __builtin_amdgcn_sched_barrier(0);          \
+    }
+#define C2R_KSTEP(SET, CKT, CST, P0, NCP)           \
+    do {                                            \
+        __builtin_amdgcn_sched_barrier(0);          \
+        C2R_MFMA(SET, 0, 0);                        \
+        C2R_MFMA(SET, 0, 1);                        \
+        C2R_COPY_IF(0, NCP, CKT, CST, P0)           \
+        C2R_MFMA(SET, 1, 0);                        \
+        C2R_MFMA(SET, 1, 1);                        \
+        C2R_COPY_IF(1, NCP, CKT, CST, P0)           \
+        C2R_MFMA(SET, 2, 0);                        \
+        C2R_MFMA(SET, 2, 1);                        \
+        C2R_COPY_IF(2, NCP, CKT, CST, P0)           \
+        C2R_MFMA(SET, 3, 0);                        \
+        C2R_MFMA(SET, 3, 1);                        \
+        C2R_COPY_IF(3, NCP, CKT, CST, P0)           \
+        __builtin_amdgcn_sched_barrier(0);          \
+    } while (0)
+
+    // One 64-wide slice = four k-steps.  The hand-over barrier sits before the LAST k-step:
+    // by then the copy of the next slice has landed and every wave has finished reading this
+    // slice's stage.  After it, the copy of the slice after next starts going into this stage
+    // (3 pieces in the last k-step here, 3 + 2 in the first two k-steps of the next slice,
+    // none in the third so that they land before the next barrier), and the first fragments
+    // of the next slice are read while the last k-step's MFMAs run, so the MFMA stream
+    // never starts a slice by waiting on LDS.
+    auto slice_step = [&](int kt, unsigned char *cur, unsigned char *nxt) {
+#ifndef C2R_CPA
+#define C2R_CPA 3
+#define C2R_CPB 3
+#define C2R_CPC 2
+#define C2R_CPD 0
+#endif
+        static_assert(C2R_CPA + C2R_CPB + C2R_CPC + C2R_CPD == 8, "all pieces scheduled");
+        const bool c1 = kt + 1 < nk;
+        const int n1 = c1 ? C2R_CPB : 0, n1b = c1 ? C2R_CPC : 0, n1c = c1 ? C2R_CPD : 0, n2 = kt + 2 < nk ? C2R_CPA : 0;
         if (active) {
-            read_frags(cur, 0, 0);
-#pragma unroll
-            for (int kk = 0; kk < NKK; ++kk) {
-                if (kk + 1 < NKK) read_frags(cur, kk + 1, (kk + 1) & 1);
-                __builtin_amdgcn_sched_barrier(0);
-                mfma_set(kk & 1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
+            read_frags(cur, 1, 1);
+            C2R_KSTEP(0, kt + 1, nxt, C2R_CPA, n1);
+            read_frags(cur, 2, 0);
+            C2R_KSTEP(1, kt + 1, nxt, C2R_CPA + C2R_CPB, n1b);
+            read_frags(cur, 3, 1);
+            C2R_KSTEP(0, kt + 1, nxt, C2R_CPA + C2R_CPB + C2R_CPC, n1c);
+        } else if (c1) {
+            if (C2R_CPA <= 1) copy_piece(kt + 1, nxt, 1);
+            if (C2R_CPA <= 2) copy_piece(kt + 1, nxt, 2);
+            if (C2R_CPA <= 3) copy_piece(kt + 1, nxt, 3);
+            copy_piece(kt + 1, nxt, 4);
+            copy_piece(kt + 1, nxt, 5);
+            copy_piece(kt + 1, nxt, 6);
+            copy_piece(kt + 1, nxt, 7);
         }
-        wait_copies_but<0>();
+        wait_copies_and_lds();  // my copies of slice kt+1 landed, my reads of `cur` returned
         lds_barrier();
+        if (active) {
+            if (kt + 1 < nk) read_frags(nxt, 0, 0);
+            C2R_KSTEP(1, kt + 2, cur, 0, n2);
+        } else if (n2) {
+            copy_piece(kt + 2, cur, 0);
+            if (C2R_CPA > 1) copy_piece(kt + 2, cur, 1);
+            if (C2R_CPA > 2) copy_piece(kt + 2, cur, 2);
+            if (C2R_CPA > 3) copy_piece(kt + 2, cur, 3);
+        }
     };
 
-    copy_slice(0, st0);
+    copy_piece(0, st0, 0);
+    copy_piece(0, st0, 1);
+    copy_piece(0, st0, 2);
+    copy_piece(0, st0, 3);
+    copy_piece(0, st0, 4);
+    copy_piece(0, st0, 5);
+    copy_piece(0, st0, 6);
+    copy_piece(0, st0, 7);
     wait_copies_but<0>();
     lds_barrier();
+    if (nk > 1) {
+        copy_piece(1, st1, 0);
+        if (C2R_CPA > 1) copy_piece(1, st1, 1);
+        if (C2R_CPA > 2) copy_piece(1, st1, 2);
+        if (C2R_CPA > 3) copy_piece(1, st1, 3);
+    }
+    if (active) read_frags(st0, 0, 0);
     for (int kt = 0; kt < nk; kt += 2) {
         slice_step(kt, st0, st1);
         if (kt + 1 >= nk) break;
         slice_step(kt + 1, st1, st0);
     }
+    wait_copies_but<0>();
+#undef C2R_KSTEP
+#undef C2R_COPY_IF
+#undef C2R_MFMA
 
     // ---- epilogue.  Fragment (i, j) holds C^T: lane (fr, fh), register v is
     //      row m = i*32 + fr, column n = j*32 + 8*(v/4) + 4*fh + v%4  -> 8-byte stores ----
