@@ -55,6 +55,14 @@ __device__ __forceinline__ void wait_copies_and_lds() {
 #endif
 }
 
+// Same, and this wave's LDS reads have returned (lgkmcnt(0)).
+template <int N>
+__device__ __forceinline__ void wait_copies_but_and_lds() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0x0070 | (N & 15) | ((N >> 4) << 14));
+#endif
+}
+
 // Bare workgroup barrier.  __syncthreads() (and any workgroup fence) also drains every
 // outstanding copy (vmcnt(0)), which would serialise the slices in flight; here the
 // caller states exactly which copies must have landed (wait_copies_but) and the
@@ -83,8 +91,15 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     constexpr int NKK = BK / 16;
     static_assert(MODE == 1 || FN % 2 == 0, "gate/up fragments pair up");
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "copy groups divide evenly");
-    __shared__ __attribute__((aligned(1024))) unsigned char st0[STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char st1[STAGE_BYTES];
+    // Short tiles (<= LM rows, i.e. small experts) are bound by streaming their expert's
+    // weights from HBM, not by the MFMAs: they use the same LDS as a three-stage ring of
+    // (LM A rows + BN B rows), two slices in flight instead of one.
+    constexpr int LM = 128, L_A_BYTES = LM * ROWB, L_STAGE_BYTES = (LM + BN) * ROWB, L_NSTAGE = 3;
+    constexpr int L_GA = LM / 8 / NW;  // A copy groups per wave on the short path
+    constexpr int SMEM_BYTES = 2 * STAGE_BYTES > L_NSTAGE * L_STAGE_BYTES ? 2 * STAGE_BYTES : L_NSTAGE * L_STAGE_BYTES;
+    static_assert(LM == TM && (LM / 8) % NW == 0, "the short path is the first wave row's M range");
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
+    unsigned char *const st0 = smem, *const st1 = smem + STAGE_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -97,6 +112,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     if (g.expert < 0) return;
     const int n0 = tl.nt * BNF;
     const int rows = g.row_end - g.row_begin;  // >= 1; may exceed BM
+    const bool short_tile = rows <= LM;        // workgroup-uniform
 
     // ---- copy roles: one copy instruction fills 8 tile rows (1024 bytes); lane l lands on
     //      row l/8, chunk position l%8 and therefore fetches chunk (l%8) ^ key(row) ----
@@ -111,7 +127,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     uint32_t offA[GA], offB[GB], rowB[GB];
 #pragma unroll
     for (int i = 0; i < GA; ++i) {
-        const int rg = wave * GA + i;
+        const int rg = short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
         int r = rg * 8 + lrow;
         r = r < rows ? r : rows - 1;
         offA[i] = (uint32_t)r * (uint32_t)lda * 2u + (uint32_t)chunkc[rg & 1] * 16u;
@@ -167,7 +183,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             r = (j < FN / 2) ? wn * (TN / 2) + j * 32 : BN / 2 + wn * (TN / 2) + (j - FN / 2) * 32;
         else
             r = wn * TN + j * 32;
-        rdB[j] = (uint32_t)A_BYTES + (uint32_t)(r + fr) * ROWB;
+        rdB[j] = (uint32_t)(short_tile ? L_A_BYTES : A_BYTES) + (uint32_t)(r + fr) * ROWB;
     }
     const int sw = swz_key(fr);
     // waves whose whole M range lies past the group's end only help with the copies
@@ -257,29 +273,77 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         }
     };
 
-    copy_piece(0, st0, 0);
-    copy_piece(0, st0, 1);
-    copy_piece(0, st0, 2);
-    copy_piece(0, st0, 3);
-    copy_piece(0, st0, 4);
-    copy_piece(0, st0, 5);
-    copy_piece(0, st0, 6);
-    copy_piece(0, st0, 7);
-    wait_copies_but<0>();
-    lds_barrier();
-    if (nk > 1) {
-        copy_piece(1, st1, 0);
-        if (C2R_CPA > 1) copy_piece(1, st1, 1);
-        if (C2R_CPA > 2) copy_piece(1, st1, 2);
-        if (C2R_CPA > 3) copy_piece(1, st1, 3);
+    if (short_tile) {
+        // ---- short tile: three-stage ring, two slices in flight, one barrier per slice ----
+        static_assert(L_GA == 2 && GB == 4, "six copies per wave per slice below");
+        auto short_copy = [&](int kt) {
+            unsigned char *stage = smem + (kt % L_NSTAGE) * L_STAGE_BYTES;
+            const uint32_t kb = (uint32_t)kt * ROWB;
+            copy16_to_lds(baseA + offA[0] + kb, stage + (wave * L_GA + 0) * 1024);
+            copy16_to_lds(baseA + offA[1] + kb, stage + (wave * L_GA + 1) * 1024);
+            const bool last = ktail && kt == nk - 1;
+            const bool clamp0 = last && kt * BK + chunkc[0] * 8 >= Kdim, clamp1 = last && kt * BK + chunkc[1] * 8 >= Kdim;
+            unsigned char *sb = stage + L_A_BYTES + wave * GB * 1024;  // wave * GB is even: groups alternate parity
+            copy16_to_lds(baseB + (clamp0 ? rowB[0] : offB[0] + kb), sb);
+            copy16_to_lds(baseB + (clamp1 ? rowB[1] : offB[1] + kb), sb + 1024);
+            copy16_to_lds(baseB + (clamp0 ? rowB[2] : offB[2] + kb), sb + 2048);
+            copy16_to_lds(baseB + (clamp1 ? rowB[3] : offB[3] + kb), sb + 3072);
+        };
+        const bool upper = rows > 64;  // fragments 2, 3 of the M range exist
+        short_copy(0);
+        if (nk > 1) short_copy(1);
+        for (int kt = 0; kt < nk; ++kt) {
+            // slice kt has landed once at most the copies of slice kt+1 are outstanding; every
+            // wave's reads of slice kt-1 have returned, so its stage may be refilled
+            if (kt + 1 < nk)
+                wait_copies_but_and_lds<6>();
+            else
+                wait_copies_but_and_lds<0>();
+            lds_barrier();
+            if (kt + 2 < nk) short_copy(kt + 2);
+            if (wm == 0) {
+                const unsigned char *stage = smem + (kt % L_NSTAGE) * L_STAGE_BYTES;
+#pragma unroll
+                for (int kk = 0; kk < NKK; ++kk) {
+                    read_frags(stage, kk, 0);
+                    C2R_MFMA(0, 0, 0);
+                    C2R_MFMA(0, 0, 1);
+                    C2R_MFMA(0, 1, 0);
+                    C2R_MFMA(0, 1, 1);
+                    if (upper) {
+                        C2R_MFMA(0, 2, 0);
+                        C2R_MFMA(0, 2, 1);
+                        C2R_MFMA(0, 3, 0);
+                        C2R_MFMA(0, 3, 1);
+                    }
+                }
+            }
+        }
+    } else {
+        copy_piece(0, st0, 0);
+        copy_piece(0, st0, 1);
+        copy_piece(0, st0, 2);
+        copy_piece(0, st0, 3);
+        copy_piece(0, st0, 4);
+        copy_piece(0, st0, 5);
+        copy_piece(0, st0, 6);
+        copy_piece(0, st0, 7);
+        wait_copies_but<0>();
+        lds_barrier();
+        if (nk > 1) {
+            copy_piece(1, st1, 0);
+            if (C2R_CPA > 1) copy_piece(1, st1, 1);
+            if (C2R_CPA > 2) copy_piece(1, st1, 2);
+            if (C2R_CPA > 3) copy_piece(1, st1, 3);
+        }
+        if (active) read_frags(st0, 0, 0);
+        for (int kt = 0; kt < nk; kt += 2) {
+            slice_step(kt, st0, st1);
+            if (kt + 1 >= nk) break;
+            slice_step(kt + 1, st1, st0);
+        }
+        wait_copies_but<0>();
     }
-    if (active) read_frags(st0, 0, 0);
-    for (int kt = 0; kt < nk; kt += 2) {
-        slice_step(kt, st0, st1);
-        if (kt + 1 >= nk) break;
-        slice_step(kt + 1, st1, st0);
-    }
-    wait_copies_but<0>();
 #undef C2R_KSTEP
 #undef C2R_COPY_IF
 #undef C2R_MFMA
