@@ -1,124 +1,150 @@
 // Router logits (Eq. 1) and collaboration-constrained selection (Sec. 3.3, step 2).
 //
 // Two kernels.
-//  route_partial_kernel: lane = token.  One wave owns 64 tokens and one 256-long
-//    k-chunk; it stages x through LDS (coalesced 16-byte loads, conflict-free
-//    per-lane row reads) and keeps one fp32 accumulator per expert in VGPRs.
-//    The W_g row for the current k is wave-uniform, so it is fetched with scalar
-//    loads and used as the SGPR operand of v_fma_f32.  The accumulation order
-//    inside a chunk is exactly the ABI's declared order (one fma per k,
-//    ascending).  Chunk results go to scratch as part[tile][chunk][expert][64]
-//    (token fastest: coalesced both here and in the reader, and one tile's
-//    partials are one contiguous run).  When there are few token tiles the
-//    experts are also split over several waves so that every SIMD has work.
-//  route_select_kernel: lane = token.  Adds the chunk results left to right,
-//    adds the bias, then does arg max / masked top-(K-1) entirely in registers
-//    with one 64-bit collaborator mask per expert held in LDS.
+//  route_partial_kernel: a register-tiled fp32 GEMM over one 256-long k-chunk; every
+//    (token, expert) pair belongs to one thread, which accumulates it with one fma per k
+//    in ascending k - exactly the ABI's declared order.  Chunk results go to scratch as
+//    part[tile][chunk][expert][64] (token fastest, one tile's partials contiguous).
+//  route_select_kernel: lane = token.  Adds the chunk results left to right, adds the
+//    bias, then does arg max / masked top-(K-1) entirely in registers with one 64-bit
+//    collaborator mask per expert held in LDS.
 #include "c2r_internal.h"
 
 namespace c2r {
 
-// Wp[s][k][j] = W_g[k][s*epw + j] (zero past E): each expert split gets its own dense
-// [d, epw] matrix, so a wave streams its W rows as one contiguous run of scalar loads.
+// Wp[k][j] = W_g[k][j] zero-padded to a row length that is a multiple of 4 (only needed when
+// E is not one), so that W rows can be fetched with 16-byte loads.
 __global__ __launch_bounds__(256) void pack_router_kernel(const float *__restrict__ Wg, int d, int E,
-                                                          int epw, int esplit, float *__restrict__ Wp) {
+                                                          int ep, float *__restrict__ Wp) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= (int64_t)d * epw * esplit) return;
-    const int j = (int)(i % epw);
-    const int k = (int)((i / epw) % d);
-    const int s = (int)(i / ((int64_t)epw * d));
-    const int e = s * epw + j;
-    Wp[i] = e < E ? Wg[(int64_t)k * E + e] : 0.0f;
+    if (i >= (int64_t)d * ep) return;
+    const int j = (int)(i % ep), k = (int)(i / ep);
+    Wp[i] = j < E ? Wg[(int64_t)k * E + j] : 0.0f;
 }
 
-template <bool BF16, int EP>  // EP: experts handled by one wave
-__global__ __launch_bounds__(64) void route_partial_kernel(const void *__restrict__ x,
-                                                           const float *__restrict__ W,
-                                                           int64_t T, int d, int nchunk, int esplit,
-                                                           int ep_total, int64_t ntiles,
-                                                           float *__restrict__ part) {
-    constexpr int VEC = BF16 ? 8 : 4;  // elements per 16-byte vector
-    constexpr int KSUB = 8 * VEC;      // elements per staged row segment (128 bytes)
-    constexpr int PITCH = 128 + 16;    // LDS row pitch in bytes: odd multiple of 16 -> no conflicts
+// Partial logits of one 256-long k-chunk for NWV 64-token tiles (one per wave), all experts.
+// A register-tiled fp32 GEMM: lane = (token lane tl, expert lane el) on an 8 x 8 grid; the
+// thread owns tokens tl + 8q (q < 8) and experts el*TE + j (j < TE), i.e. 8*TE accumulators,
+// and walks k upward one fused multiply-add at a time, which is the declared order.  Both
+// operands come from LDS (x as stored, 16 bytes = 8 bf16 or 4 fp32 per token per read; W
+// rows as fp32), staged in 32-wide k sub-tiles that are double buffered against global
+// loads held in registers; the W sub-tile is shared by the workgroup's waves.
+template <bool BF16, int TE, int NWV>
+__global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__restrict__ x,
+                                                                const float *__restrict__ W, int ldw,
+                                                                int ep, int64_t T, int d, int nchunk,
+                                                                int64_t ntiles,
+                                                                float *__restrict__ part) {
+    constexpr int EPAD = 8 * TE;         // experts covered by a wave
+    constexpr int KS = 32;               // k per staged sub-tile
+    constexpr int VEC = BF16 ? 8 : 4;    // elements per 16-byte vector of x
     constexpr int ESZ = BF16 ? 2 : 4;
-    __shared__ __attribute__((aligned(16))) unsigned char lds[2][64 * PITCH];
+    constexpr int XV = KS / VEC;         // 16-byte vectors per token per sub-tile
+    constexpr int XPITCH = KS * ESZ + 16;  // bytes; token rows 8 apart land on distinct bank groups
+    constexpr int XLOADS = 64 * XV / 64;   // vectors per lane per sub-tile
+    constexpr int WF4 = KS * EPAD / 4;     // float4 per W sub-tile
+    constexpr int WLOADS = (WF4 + NWV * 64 - 1) / (NWV * 64);
+    __shared__ __attribute__((aligned(16))) float Wl[2][KS][EPAD];
+    __shared__ __attribute__((aligned(16))) unsigned char Xl[2][NWV][64 * XPITCH];
 
-    const int lane = threadIdx.x;
-    // token tile fastest: the workgroups dispatched together share one (chunk, split), i.e. the
-    // same W rows, which then stay hot in the scalar cache and L2
-    const int64_t tile = blockIdx.x % ntiles;
-    const int cs = (int)(blockIdx.x / ntiles);
-    const int split = cs % esplit, chunk = cs / esplit;
-    W += (size_t)split * d * EP;  // this split's dense [d, EP] matrix
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int tl = lane & 7, el = lane >> 3;
+    const int64_t ngroups = (ntiles + NWV - 1) / NWV;
+    const int64_t tgroup = blockIdx.x % ngroups;  // token tiles fastest: neighbours share W rows in L2
+    const int chunk = (int)(blockIdx.x / ngroups);
+    const int64_t tile = tgroup * NWV + wave;      // may be >= ntiles: such a wave only helps load W
+    const bool live = tile < ntiles;
     const int k_begin = chunk * C2R_CANON_CHUNK;
     const int k_end = min(d, k_begin + C2R_CANON_CHUNK);
     const int64_t t0 = tile * 64;
-    const int lrow = lane >> 3, lc = lane & 7;
     const unsigned char *xb = static_cast<const unsigned char *>(x);
 
-    uint4 stage[8];
+    float4 wreg[WLOADS];
+    uint4 xreg[XLOADS];
     auto gload = [&](int k0) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            int64_t t = t0 + lrow + 8 * i;
-            t = t < T ? t : T - 1;  // rows past the end re-read the last token; never stored
-            int kc = k0 + lc * VEC;
-            if (kc < k_end)
-                stage[i] = *reinterpret_cast<const uint4 *>(xb + ((size_t)t * d + kc) * ESZ);
-            else
-                stage[i] = make_uint4(0, 0, 0, 0);
+        for (int i = 0; i < WLOADS; ++i) {
+            const int idx = tid + i * NWV * 64;
+            const int k = idx / (EPAD / 4), c = idx % (EPAD / 4);
+            wreg[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (idx < WF4 && k0 + k < k_end && c * 4 < ep)
+                wreg[i] = *reinterpret_cast<const float4 *>(W + (size_t)(k0 + k) * ldw + c * 4);
+        }
+#pragma unroll
+        for (int i = 0; i < XLOADS; ++i) {
+            const int idx = lane + i * 64;
+            const int tok = idx / XV, c = idx % XV;
+            int64_t t = t0 + tok;
+            t = t < T ? t : T - 1;  // rows past the end (and dead waves) re-read a valid token
+            t = t < 0 ? 0 : t;
+            const int kc = k0 + c * VEC;
+            xreg[i] = make_uint4(0, 0, 0, 0);
+            if (kc < k_end) xreg[i] = *reinterpret_cast<const uint4 *>(xb + ((size_t)t * d + kc) * ESZ);
         }
     };
     auto lstore = [&](int buf) {
 #pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<uint4 *>(&lds[buf][(lrow + 8 * i) * PITCH + lc * 16]) = stage[i];
+        for (int i = 0; i < WLOADS; ++i) {
+            const int idx = tid + i * NWV * 64;
+            if (idx < WF4) *reinterpret_cast<float4 *>(&Wl[buf][idx / (EPAD / 4)][(idx % (EPAD / 4)) * 4]) = wreg[i];
+        }
+#pragma unroll
+        for (int i = 0; i < XLOADS; ++i) {
+            const int idx = lane + i * 64;
+            *reinterpret_cast<uint4 *>(&Xl[buf][wave][(idx / XV) * XPITCH + (idx % XV) * 16]) = xreg[i];
+        }
     };
 
-    float acc[EP];
+    float acc[8][TE];
 #pragma unroll
-    for (int e = 0; e < EP; ++e) acc[e] = 0.0f;
+    for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int j = 0; j < TE; ++j) acc[q][j] = 0.0f;
 
     gload(k_begin);
     lstore(0);
     __syncthreads();
     int buf = 0;
-    for (int k0 = k_begin; k0 < k_end; k0 += KSUB) {
-        const int knext = k0 + KSUB;
+    for (int k0 = k_begin; k0 < k_end; k0 += KS) {
+        const int knext = k0 + KS;
         if (knext < k_end) gload(knext);
-        const int nvec = min(KSUB, k_end - k0) / VEC;
+        const int nvec = min(KS, k_end - k0) / VEC;  // workgroup-uniform
         for (int v = 0; v < nvec; ++v) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(&lds[buf][lane * PITCH + v * 16]);
-            float xv[VEC];
-            if constexpr (BF16) {
-                xv[0] = __uint_as_float(raw.x << 16);
-                xv[1] = __uint_as_float(raw.x & 0xffff0000u);
-                xv[2] = __uint_as_float(raw.y << 16);
-                xv[3] = __uint_as_float(raw.y & 0xffff0000u);
-                xv[4] = __uint_as_float(raw.z << 16);
-                xv[5] = __uint_as_float(raw.z & 0xffff0000u);
-                xv[6] = __uint_as_float(raw.w << 16);
-                xv[7] = __uint_as_float(raw.w & 0xffff0000u);
-            } else {
-                xv[0] = __uint_as_float(raw.x);
-                xv[1] = __uint_as_float(raw.y);
-                xv[2] = __uint_as_float(raw.z);
-                xv[3] = __uint_as_float(raw.w);
-            }
+            uint4 xp[8];
 #pragma unroll
-            for (int j = 0; j < VEC; ++j) {
-                const float *__restrict__ wrow = W + (size_t)(k0 + v * VEC + j) * EP;
+            for (int q = 0; q < 8; ++q)
+                xp[q] = *reinterpret_cast<const uint4 *>(&Xl[buf][wave][(tl + 8 * q) * XPITCH + v * 16]);
 #pragma unroll
-                for (int e = 0; e < EP; ++e) acc[e] = __builtin_fmaf(xv[j], wrow[e], acc[e]);
+            for (int u = 0; u < VEC; ++u) {
+                float wv[TE];
+#pragma unroll
+                for (int j = 0; j < TE; ++j) wv[j] = Wl[buf][v * VEC + u][el * TE + j];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    const uint32_t word = BF16 ? (u < 2 ? xp[q].x : u < 4 ? xp[q].y : u < 6 ? xp[q].z : xp[q].w)
+                                               : (u == 0 ? xp[q].x : u == 1 ? xp[q].y : u == 2 ? xp[q].z : xp[q].w);
+                    const float xv = BF16 ? __uint_as_float((u & 1) ? (word & 0xffff0000u) : (word << 16))
+                                          : __uint_as_float(word);
+#pragma unroll
+                    for (int j = 0; j < TE; ++j) acc[q][j] = __builtin_fmaf(xv, wv[j], acc[q][j]);
+                }
             }
         }
         if (knext < k_end) lstore(buf ^ 1);
         __syncthreads();
         buf ^= 1;
     }
-    float *dst = part + (((size_t)tile * nchunk + chunk) * ep_total + split * EP) * 64 + lane;
+    if (!live) return;
+    float *dst = part + (((size_t)tile * nchunk + chunk) * ep) * 64;
 #pragma unroll
-    for (int e = 0; e < EP; ++e) dst[e * 64] = acc[e];
+    for (int j = 0; j < TE; ++j) {
+        const int e = el * TE + j;
+        if (e < ep) {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) dst[(size_t)e * 64 + tl + 8 * q] = acc[q][j];
+        }
+    }
 }
 
 // Among experts whose bit is set in m: the largest logit, first one standing
@@ -253,7 +279,7 @@ static int check_route_args(int64_t T, int E, int K, const int32_t *collab_idx, 
 static inline int ep_of(int E) { return (E + 3) / 4 * 4; }
 
 struct RouteLayout {
-    int EP, nchunk, esplit;
+    int EP, nchunk;
     int64_t Tpad;
     size_t part_bytes, wpad_bytes;
 };
@@ -264,18 +290,8 @@ static RouteLayout route_layout(int64_t T, int d, int E) {
     L.nchunk = (d + C2R_CANON_CHUNK - 1) / C2R_CANON_CHUNK;
     if (L.nchunk < 1) L.nchunk = 1;
     L.Tpad = (T + 63) / 64 * 64;
-    // split the experts over `esplit` waves (each a multiple of 4 experts, at least 8) until
-    // there are about two waves per SIMD (256 CUs x 4 SIMDs)
-    L.esplit = 1;
-    const int64_t base_waves = L.Tpad / 64 * L.nchunk;
-    for (int s = 1; s <= L.EP / 4; ++s) {
-        if ((L.EP / 4) % s != 0) continue;
-        if (L.EP / s < 8 && s > 1) break;
-        L.esplit = s;
-        if (base_waves * s >= 2048) break;
-    }
     L.part_bytes = round_up((size_t)L.nchunk * L.EP * (size_t)L.Tpad * sizeof(float), 256);
-    L.wpad_bytes = (E % 4 || L.esplit > 1) ? round_up((size_t)d * L.EP * sizeof(float), 256) : 0;
+    L.wpad_bytes = (E % 4) ? round_up((size_t)d * L.EP * sizeof(float), 256) : 0;
     return L;
 }
 
@@ -328,23 +344,41 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
     hipStream_t st = static_cast<hipStream_t>(stream);
     float *part = static_cast<float *>(ws);
     const float *W = Wg;
-    const int EPW = L.EP / L.esplit;
+    int ldw = E;
     if (L.wpad_bytes) {
         float *Wp = reinterpret_cast<float *>(static_cast<char *>(ws) + L.part_bytes);
         const int64_t n = (int64_t)d * L.EP;
-        pack_router_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(Wg, d, E, EPW, L.esplit, Wp);
+        pack_router_kernel<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st>>>(Wg, d, E, L.EP, Wp);
         W = Wp;
+        ldw = L.EP;
+    } else if (!aligned(Wg, 16)) {
+        return C2R_ERR_INVALID_ARG;
     }
     const int64_t ntiles = L.Tpad / 64;
-    const int64_t nblk = ntiles * L.nchunk * L.esplit;
+    // waves per workgroup share the W sub-tiles; with few token tiles use fewer waves per
+    // workgroup so that the launch still spreads over the CUs
+    const int te = L.EP > 32 ? 8 : L.EP > 16 ? 4 : L.EP > 8 ? 2 : 1;
+    const bool wide = ntiles * L.nchunk >= 2048;
+    const int nwv = wide ? 4 : 2;
+    const int64_t nblk = (ntiles + nwv - 1) / nwv * L.nchunk;
     if (nblk >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
-    if (x_dt == C2R_BF16) {
-        C2R_EP_SWITCH(EPW, route_partial_kernel<true, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
-                               x, W, T, d, L.nchunk, L.esplit, L.EP, ntiles, part));
-    } else {
-        C2R_EP_SWITCH(EPW, route_partial_kernel<false, EP><<<dim3((unsigned)nblk), dim3(64), 0, st>>>(
-                               x, W, T, d, L.nchunk, L.esplit, L.EP, ntiles, part));
+#define C2R_ROUTE_LAUNCH(BF, TE, NWV)                                                             \
+    route_partial_kernel<BF, TE, NWV><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(            \
+        x, W, ldw, L.EP, T, d, L.nchunk, ntiles, part)
+#define C2R_ROUTE_TE(BF, NWV)                          \
+    switch (te) {                                      \
+        case 8: C2R_ROUTE_LAUNCH(BF, 8, NWV); break;   \
+        case 4: C2R_ROUTE_LAUNCH(BF, 4, NWV); break;   \
+        case 2: C2R_ROUTE_LAUNCH(BF, 2, NWV); break;   \
+        default: C2R_ROUTE_LAUNCH(BF, 1, NWV); break;  \
     }
+    if (x_dt == C2R_BF16) {
+        if (wide) { C2R_ROUTE_TE(true, 4) } else { C2R_ROUTE_TE(true, 2) }
+    } else {
+        if (wide) { C2R_ROUTE_TE(false, 4) } else { C2R_ROUTE_TE(false, 2) }
+    }
+#undef C2R_ROUTE_TE
+#undef C2R_ROUTE_LAUNCH
     C2R_EP_SWITCH(L.EP, route_select_kernel<EP, false><<<dim3((unsigned)ntiles), dim3(64), 0, st>>>(
                             part, L.nchunk, bias, T, E, K, collab_idx, Tc, topk_idx, gates, logits_out));
     return launch_status();

@@ -33,8 +33,9 @@ def test_workspace_query_is_host_only():
     c2r = _lib()
     assert c2r.workspace_bytes(c2r.STAGE_COACTIVATION, 1000, 64, 8, 2, 0, c2r.F32) == 0
     # route scratch: one fp32 per (chunk, expert, token padded to 64)
-    # (+ a per-split repacked copy of W_g when the experts are split over several waves)
-    assert c2r.workspace_bytes(c2r.STAGE_ROUTE, 8192, 2048, 60, 4, 0, c2r.BF16) == 8 * 60 * 8192 * 4 + 2048 * 60 * 4
+    assert c2r.workspace_bytes(c2r.STAGE_ROUTE, 8192, 2048, 60, 4, 0, c2r.BF16) == 8 * 60 * 8192 * 4
+    # (+ a zero-padded copy of W_g when E is not a multiple of 4)
+    assert c2r.workspace_bytes(c2r.STAGE_ROUTE, 64, 256, 7, 2, 0, c2r.F32) == 1 * 8 * 64 * 4 + 256 * 8 * 4
     assert c2r.workspace_bytes(c2r.STAGE_ROUTE, 100, 256, 8, 2, 0, c2r.F32) == 1 * 8 * 128 * 4
     assert c2r.workspace_bytes(c2r.STAGE_EXPERT_FFN, 32768, 2048, 60, 1, 1408, c2r.BF16) == 32768 * 1408 * 2
     assert c2r.workspace_bytes(c2r.STAGE_EXPERT_FFN, 100, 4096, 16, 1, 688, c2r.BF16) == 100 * 704 * 2 + 0 * 256
