@@ -3,7 +3,8 @@
 //
 //  1. permute_hist_kernel   per-block LDS histogram of local slots
 //  2. permute_scan_kernel   counts, exclusive offsets, and the start position of
-//                           every (block, slot) run
+//                           every (block, slot) run (folded into step 3 when there are
+//                           few blocks: each block sums the histograms it needs itself)
 //  3. permute_rank_kernel   stable rank inside the block: each wave step ranks
 //                           its 64 assignments with ballots (equal keys keep
 //                           lane order), an LDS prefix over the block's wave
@@ -77,11 +78,51 @@ __global__ __launch_bounds__(64) void permute_scan_kernel(const int32_t *__restr
     }
 }
 
+// FUSED: there are few blocks, so every block derives the run starts itself from the block
+// histograms (and block 0 also writes counts / offsets) instead of a separate scan launch.
+template <bool FUSED>
 __global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(
     const int32_t *__restrict__ topk_idx, int64_t A, int E, const int32_t *__restrict__ local_slot,
-    int E_local, const int32_t *__restrict__ block_base, int32_t *__restrict__ perm,
-    int32_t *__restrict__ inv_perm) {
+    int E_local, const int32_t *__restrict__ block_base, const int32_t *__restrict__ block_counts,
+    int nblocks, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
+    int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm) {
     __shared__ int32_t step_cnt[PB_STEPS][C2R_MAX_E];
+    __shared__ int32_t part_tot[PB_THREADS / 64][C2R_MAX_E], part_pre[PB_THREADS / 64][C2R_MAX_E];
+    __shared__ int32_t run_base[C2R_MAX_E];
+    if (FUSED) {
+        const int e = threadIdx.x & 63, part = threadIdx.x >> 6;
+        int32_t tot = 0, pre = 0;
+        if (e < E_local) {
+            for (int b = part; b < nblocks; b += PB_THREADS / 64) {
+                const int32_t v = block_counts[(size_t)b * E_local + e];
+                tot += v;
+                if (b < (int)blockIdx.x) pre += v;
+            }
+        }
+        part_tot[part][e] = tot;
+        part_pre[part][e] = pre;
+        __syncthreads();
+        if (threadIdx.x < 64) {
+            int32_t total = 0, before = 0;
+#pragma unroll
+            for (int q = 0; q < PB_THREADS / 64; ++q) {
+                total += part_tot[q][e];
+                before += part_pre[q][e];
+            }
+            int32_t incl = total;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int32_t v = __shfl_up(incl, off);
+                if (e >= off) incl += v;
+            }
+            run_base[e] = incl - total + before;
+            if (blockIdx.x == 0 && e < E_local) {
+                counts[e] = total;
+                offsets[e] = incl - total;
+                if (e == E_local - 1) offsets[E_local] = incl;
+            }
+        }
+    }
     for (int i = threadIdx.x; i < PB_STEPS * C2R_MAX_E; i += PB_THREADS) (&step_cnt[0][0])[i] = 0;
     __syncthreads();
 
@@ -112,7 +153,7 @@ __global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(
     __syncthreads();
     // exclusive prefix over the block's wave steps, per slot, seeded with the block's start
     if (threadIdx.x < E_local) {
-        int32_t run = block_base[(size_t)blockIdx.x * E_local + threadIdx.x];
+        int32_t run = FUSED ? run_base[threadIdx.x] : block_base[(size_t)blockIdx.x * E_local + threadIdx.x];
 #pragma unroll
         for (int q = 0; q < PB_STEPS; ++q) {
             const int32_t c = step_cnt[q][threadIdx.x];
@@ -206,11 +247,19 @@ extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx,
     if (nblocks > 0)
         permute_hist_kernel<<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
             topk_idx, A, E, local_slot, E_local, block_counts);
-    permute_scan_kernel<<<dim3(1), dim3(64), 0, st>>>(block_counts, (int)nblocks, E_local, block_base,
-                                                      counts, offsets);
+    const bool fused = nblocks > 0 && nblocks <= 256;  // each block re-reads nblocks*E_local counts
+    if (!fused)
+        permute_scan_kernel<<<dim3(1), dim3(64), 0, st>>>(block_counts, (int)nblocks, E_local, block_base,
+                                                          counts, offsets);
     if (nblocks > 0) {
-        permute_rank_kernel<<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
-            topk_idx, A, E, local_slot, E_local, block_base, perm, inv_perm);
+        if (fused)
+            permute_rank_kernel<true><<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
+                topk_idx, A, E, local_slot, E_local, block_base, block_counts, (int)nblocks, counts, offsets,
+                perm, inv_perm);
+        else
+            permute_rank_kernel<false><<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
+                topk_idx, A, E, local_slot, E_local, block_base, block_counts, (int)nblocks, counts, offsets,
+                perm, inv_perm);
         if (x_perm) {
             const int row_vecs = d * (dt == C2R_BF16 ? 2 : 4) / 16;
             permute_rows_kernel<<<dim3((unsigned)((T + 3) / 4)), dim3(256), 0, st>>>(
