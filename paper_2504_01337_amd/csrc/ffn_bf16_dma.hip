@@ -1,6 +1,8 @@
 // Grouped SwiGLU expert FFN in bf16, fast path: global -> LDS copies that bypass the
 // register file (global_load_lds_dwordx4), 8 waves per workgroup, 256 x 256 output tiles,
-// 64-wide k-slices double buffered in LDS.
+// 64-wide k-slices double buffered in LDS, v_mfma_f32_16x16x32_bf16 (measured 4-8 % faster
+// here than the 32x32x16 form at equal LDS traffic: a quarter of the accumulator registers
+// move per instruction, and under this chip's power limit that buys clock).
 //
 // Same two passes, tile numbering and epilogue as the generic kernel in ffn_bf16.hip;
 // what differs is how a k-slice reaches LDS.  One wave-level copy instruction moves
@@ -83,13 +85,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     constexpr int BM = 256, BN = 256, BK = 64;
     constexpr int NW = WM * WN;                // waves
     constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
-    constexpr int FM = TM / 32, FN = TN / 32;  // 32x32 fragments per wave
     constexpr int ROWB = BK * 2;               // 128 bytes per tile row: whole cache lines per copy
     constexpr int GA = BM / 8 / NW, GB = BN / 8 / NW;  // 8-row copy groups per wave
     constexpr int A_BYTES = BM * ROWB, STAGE_BYTES = (BM + BN) * ROWB;
     constexpr int BNF = MODE == 0 ? BN / 2 : BN;
-    constexpr int NKK = BK / 16;
-    static_assert(MODE == 1 || FN % 2 == 0, "gate/up fragments pair up");
     static_assert((BM / 8) % NW == 0 && (BN / 8) % NW == 0, "copy groups divide evenly");
     // Short tiles (<= LM rows, i.e. small experts) are bound by streaming their expert's
     // weights from HBM, not by the MFMAs: they use the same LDS as a three-stage ring of
@@ -164,65 +163,76 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     };
     constexpr int NPIECE = GA + GB;
 
-    f32x16 acc[FM][FN];
+    // v_mfma_f32_16x16x32_bf16: 16 x 16 output fragments, 32 k per instruction.  A wave owns
+    // 8 x 4 of them (128 x 64 outputs); a k-step is one 32-wide k range x one 64-row half.
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    constexpr int FM16 = TM / 16, FN16 = TN / 16;
+    static_assert(FM16 == 8 && FN16 == 4, "k-step macros below");
+    f32x4 acc[FM16][FN16];
 #pragma unroll
-    for (int i = 0; i < FM; ++i)
+    for (int i = 0; i < FM16; ++i)
 #pragma unroll
-        for (int j = 0; j < FN; ++j)
+        for (int j = 0; j < FN16; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+            for (int v = 0; v < 4; ++v) acc[i][j][v] = 0.0f;
 
-    const int fr = lane & 31, fh = lane >> 5;
-    uint32_t rdA[FM], rdB[FN];
+    const int fr = lane & 15, fq = lane >> 4;
+    uint32_t rdA[FM16], rdB[FN16];
 #pragma unroll
-    for (int i = 0; i < FM; ++i) rdA[i] = (uint32_t)(wm * TM + i * 32 + fr) * ROWB;
+    for (int i = 0; i < FM16; ++i) rdA[i] = (uint32_t)(wm * TM + i * 16 + fr) * ROWB;
 #pragma unroll
-    for (int j = 0; j < FN; ++j) {
+    for (int j = 0; j < FN16; ++j) {
         int r;
         if (MODE == 0)
-            r = (j < FN / 2) ? wn * (TN / 2) + j * 32 : BN / 2 + wn * (TN / 2) + (j - FN / 2) * 32;
+            r = (j < FN16 / 2) ? wn * (TN / 2) + j * 16 : BN / 2 + wn * (TN / 2) + (j - FN16 / 2) * 16;
         else
-            r = wn * TN + j * 32;
+            r = wn * TN + j * 16;
         rdB[j] = (uint32_t)(short_tile ? L_A_BYTES : A_BYTES) + (uint32_t)(r + fr) * ROWB;
     }
     const int sw = swz_key(fr);
     // waves whose whole M range lies past the group's end only help with the copies
     const bool active = __builtin_amdgcn_readfirstlane(rows - wm * TM) > 0;
 
-    bf16x8 af[2][FM], bfr[2][FN];
-    auto read_frags = [&](const unsigned char *stage, int kk, int set) {
-        const uint32_t ch = (uint32_t)(((kk * 2 + fh) ^ sw) * 16);
+    bf16x8 aset[2][4], bset[2][4];
+    // A fragments of k range kq (0, 1) and 64-row half `half` into set `set`
+    auto read_a = [&](const unsigned char *stage, int kq, int half, int set) {
+        const uint32_t ch = (uint32_t)(((kq * 4 + fq) ^ sw) * 16);
 #pragma unroll
-        for (int i = 0; i < FM; ++i) af[set][i] = *reinterpret_cast<const bf16x8 *>(stage + rdA[i] + ch);
-#pragma unroll
-        for (int j = 0; j < FN; ++j) bfr[set][j] = *reinterpret_cast<const bf16x8 *>(stage + rdB[j] + ch);
+        for (int i = 0; i < 4; ++i) aset[set][i] = *reinterpret_cast<const bf16x8 *>(stage + rdA[half * 4 + i] + ch);
     };
-    static_assert(NPIECE == 8 && FM == 4 && FN == 2, "copy schedule below: 3 + 3 + 2 pieces over three k-steps");
-    // MFMAs of one k-step (operands swapped: the lane's 4-element runs lie along n) with up
-    // to three copy pieces P0.. of slice CKT slipped in after every second MFMA.  Macros, so
-    // that every fragment and piece index is a literal and the arrays stay in registers.
-#define C2R_MFMA(SET, I, J) \
-    acc[I][J] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[SET][J], af[SET][I], acc[I][J], 0, 0, 0)
+    auto read_b = [&](const unsigned char *stage, int kq, int set) {
+        const uint32_t ch = (uint32_t)(((kq * 4 + fq) ^ sw) * 16);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bset[set][j] = *reinterpret_cast<const bf16x8 *>(stage + rdB[j] + ch);
+    };
+    static_assert(NPIECE == 8, "copy schedule below: 3 + 3 + 2 pieces over three k-steps");
+    // MFMAs of one k-step (operands swapped: the lane's 4 results lie along n) with up to
+    // four copy pieces P0.. of slice CKT slipped in after every fourth MFMA.  Macros, so that
+    // every fragment and piece index is a literal and the arrays stay in registers.
+#define C2R_MFMA(AS, BS, H, I, J)                                                                 \
+    acc[(H) * 4 + (I)][J] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bset[BS][J], aset[AS][I],     \
+                                                                    acc[(H) * 4 + (I)][J], 0, 0, 0)
+#define C2R_MFMA_ROW(AS, BS, H, I) \
+    C2R_MFMA(AS, BS, H, I, 0);     \
+    C2R_MFMA(AS, BS, H, I, 1);     \
+    C2R_MFMA(AS, BS, H, I, 2);     \
+    C2R_MFMA(AS, BS, H, I, 3)
 #define C2R_COPY_IF(Q, NCP, CKT, CST, P0)           \
     if ((Q) < (NCP)) {                              \
         __builtin_amdgcn_sched_barrier(0);          \
         copy_piece(CKT, CST, (P0) + (Q));           \
         __builtin_amdgcn_sched_barrier(0);          \
     }
-#define C2R_KSTEP(SET, CKT, CST, P0, NCP)           \
+#define C2R_KSTEP(AS, BS, H, CKT, CST, P0, NCP)     \
     do {                                            \
         __builtin_amdgcn_sched_barrier(0);          \
-        C2R_MFMA(SET, 0, 0);                        \
-        C2R_MFMA(SET, 0, 1);                        \
+        C2R_MFMA_ROW(AS, BS, H, 0);                 \
         C2R_COPY_IF(0, NCP, CKT, CST, P0)           \
-        C2R_MFMA(SET, 1, 0);                        \
-        C2R_MFMA(SET, 1, 1);                        \
+        C2R_MFMA_ROW(AS, BS, H, 1);                 \
         C2R_COPY_IF(1, NCP, CKT, CST, P0)           \
-        C2R_MFMA(SET, 2, 0);                        \
-        C2R_MFMA(SET, 2, 1);                        \
+        C2R_MFMA_ROW(AS, BS, H, 2);                 \
         C2R_COPY_IF(2, NCP, CKT, CST, P0)           \
-        C2R_MFMA(SET, 3, 0);                        \
-        C2R_MFMA(SET, 3, 1);                        \
+        C2R_MFMA_ROW(AS, BS, H, 3);                 \
         C2R_COPY_IF(3, NCP, CKT, CST, P0)           \
         __builtin_amdgcn_sched_barrier(0);          \
     } while (0)
@@ -245,12 +255,13 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         const bool c1 = kt + 1 < nk;
         const int n1 = c1 ? C2R_CPB : 0, n1b = c1 ? C2R_CPC : 0, n1c = c1 ? C2R_CPD : 0, n2 = kt + 2 < nk ? C2R_CPA : 0;
         if (active) {
-            read_frags(cur, 1, 1);
-            C2R_KSTEP(0, kt + 1, nxt, C2R_CPA, n1);
-            read_frags(cur, 2, 0);
-            C2R_KSTEP(1, kt + 1, nxt, C2R_CPA + C2R_CPB, n1b);
-            read_frags(cur, 3, 1);
-            C2R_KSTEP(0, kt + 1, nxt, C2R_CPA + C2R_CPB + C2R_CPC, n1c);
+            read_a(cur, 0, 1, 1);
+            C2R_KSTEP(0, 0, 0, kt + 1, nxt, C2R_CPA, n1);
+            read_a(cur, 1, 0, 0);
+            read_b(cur, 1, 1);
+            C2R_KSTEP(1, 0, 1, kt + 1, nxt, C2R_CPA + C2R_CPB, n1b);
+            read_a(cur, 1, 1, 1);
+            C2R_KSTEP(0, 1, 0, kt + 1, nxt, C2R_CPA + C2R_CPB + C2R_CPC, n1c);
         } else if (c1) {
             if (C2R_CPA <= 1) copy_piece(kt + 1, nxt, 1);
             if (C2R_CPA <= 2) copy_piece(kt + 1, nxt, 2);
@@ -263,8 +274,11 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         wait_copies_and_lds();  // my copies of slice kt+1 landed, my reads of `cur` returned
         lds_barrier();
         if (active) {
-            if (kt + 1 < nk) read_frags(nxt, 0, 0);
-            C2R_KSTEP(1, kt + 2, cur, 0, n2);
+            if (kt + 1 < nk) {
+                read_a(nxt, 0, 0, 0);
+                read_b(nxt, 0, 0);
+            }
+            C2R_KSTEP(1, 1, 1, kt + 2, cur, 0, n2);
         } else if (n2) {
             copy_piece(kt + 2, cur, 0);
             if (C2R_CPA > 1) copy_piece(kt + 2, cur, 1);
@@ -304,17 +318,19 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             if (wm == 0) {
                 const unsigned char *stage = smem + (kt % L_NSTAGE) * L_STAGE_BYTES;
 #pragma unroll
-                for (int kk = 0; kk < NKK; ++kk) {
-                    read_frags(stage, kk, 0);
-                    C2R_MFMA(0, 0, 0);
-                    C2R_MFMA(0, 0, 1);
-                    C2R_MFMA(0, 1, 0);
-                    C2R_MFMA(0, 1, 1);
+                for (int kq = 0; kq < 2; ++kq) {
+                    read_b(stage, kq, 0);
+                    read_a(stage, kq, 0, 0);
+                    C2R_MFMA_ROW(0, 0, 0, 0);
+                    C2R_MFMA_ROW(0, 0, 0, 1);
+                    C2R_MFMA_ROW(0, 0, 0, 2);
+                    C2R_MFMA_ROW(0, 0, 0, 3);
                     if (upper) {
-                        C2R_MFMA(0, 2, 0);
-                        C2R_MFMA(0, 2, 1);
-                        C2R_MFMA(0, 3, 0);
-                        C2R_MFMA(0, 3, 1);
+                        read_a(stage, kq, 1, 1);
+                        C2R_MFMA_ROW(1, 0, 1, 0);
+                        C2R_MFMA_ROW(1, 0, 1, 1);
+                        C2R_MFMA_ROW(1, 0, 1, 2);
+                        C2R_MFMA_ROW(1, 0, 1, 3);
                     }
                 }
             }
@@ -336,7 +352,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             if (C2R_CPA > 2) copy_piece(1, st1, 2);
             if (C2R_CPA > 3) copy_piece(1, st1, 3);
         }
-        if (active) read_frags(st0, 0, 0);
+        if (active) {
+            read_a(st0, 0, 0, 0);
+            read_b(st0, 0, 0);
+        }
         for (int kt = 0; kt < nk; kt += 2) {
             slice_step(kt, st0, st1);
             if (kt + 1 >= nk) break;
@@ -346,39 +365,37 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     }
 #undef C2R_KSTEP
 #undef C2R_COPY_IF
+#undef C2R_MFMA_ROW
 #undef C2R_MFMA
 
-    // ---- epilogue.  Fragment (i, j) holds C^T: lane (fr, fh), register v is
-    //      row m = i*32 + fr, column n = j*32 + 8*(v/4) + 4*fh + v%4  -> 8-byte stores ----
+    // ---- epilogue.  Fragment (i, j) holds C^T: lane (fr, fq), register v is
+    //      row m = i*16 + fr, column n = j*16 + 4*fq + v  -> 8-byte stores ----
     uint16_t *outb = out + (size_t)g.row_begin * ldo;
-    constexpr int FJ = MODE == 0 ? FN / 2 : FN;
+    constexpr int FJ = MODE == 0 ? FN16 / 2 : FN16;
 #pragma unroll
-    for (int i = 0; i < FM; ++i) {
-        const int r = wm * TM + i * 32 + fr;
+    for (int i = 0; i < FM16; ++i) {
+        const int r = wm * TM + i * 16 + fr;
         if (r >= rows) continue;
 #pragma unroll
         for (int j = 0; j < FJ; ++j) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int col = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN) + j * 32 + q * 8 + fh * 4;
-                uint2 pk = make_uint2(0, 0);
-                if (col >= N) {
-                    // pass 0 keeps the padding columns of h at zero for pass 1's k tail
-                    if (col < zero_to) *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
-                    continue;
-                }
-                float v4[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (MODE == 0)
-                        v4[u] = silu_mul(acc[i][j][q * 4 + u], acc[i][j + FN / 2][q * 4 + u]);
-                    else
-                        v4[u] = acc[i][j][q * 4 + u];
-                }
-                pk.x = pack_bf16x2(v4[0], v4[1]);
-                pk.y = pack_bf16x2(v4[2], v4[3]);
-                *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
+            const int col = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN) + j * 16 + fq * 4;
+            uint2 pk = make_uint2(0, 0);
+            if (col >= N) {
+                // pass 0 keeps the padding columns of h at zero for pass 1's k tail
+                if (col < zero_to) *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
+                continue;
             }
+            float v4[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (MODE == 0)
+                    v4[u] = silu_mul(acc[i][j][u], acc[i][j + FN16 / 2][u]);
+                else
+                    v4[u] = acc[i][j][u];
+            }
+            pk.x = pack_bf16x2(v4[0], v4[1]);
+            pk.y = pack_bf16x2(v4[2], v4[3]);
+            *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
         }
     }
 }
