@@ -46,7 +46,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_kernel(const uint16_t *_
 
     // ---- which tile ----
     const GroupMap gmap = build_group_map<BM>(offsets, E_local, A_cap);
-    const TileId tl = xcd_grouped_tile(gmap.total_mtiles, ntn);
+    const TileId tl = xcd_grouped_tile<false>(gmap.total_mtiles, ntn);
     if (!tl.valid) return;
     const int nt = tl.nt;
     const GroupTile g = locate_group_tile(gmap, tl.mt, BM);
@@ -200,7 +200,7 @@ static int launch_cfg(int pass, const uint16_t *a, const int32_t *offsets, int E
                       int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out, hipStream_t st) {
     const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
     const int ntn = pass == 0 ? (F + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
-    const int64_t grid = xcd_grouped_grid(mtiles, ntn);
+    const int64_t grid = xcd_grouped_grid(mtiles, ntn, false);
     if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (pass == 0)
         ffn_bf16_kernel<0, BM, BN, BK, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(

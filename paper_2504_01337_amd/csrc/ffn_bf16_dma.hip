@@ -105,12 +105,16 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     const int wm = wave / WN, wn = wave % WN;
 
     const GroupMap gmap = build_group_map<BM>(offsets, E_local, A_cap);
-    const TileId tl = xcd_grouped_tile(gmap.total_mtiles, ntn);
+    const TileId tl = xcd_grouped_tile<true>(gmap.total_mtiles, ntn);
     if (!tl.valid) return;
-    const GroupTile g = locate_group_tile(gmap, tl.mt, BM);
+    GroupTile g = locate_group_tile(gmap, tl.mt, BM);
     if (g.expert < 0) return;
     const int n0 = tl.nt * BNF;
-    const int rows = g.row_end - g.row_begin;  // >= 1; may exceed BM
+    // a part of a split tail tile: rows [sub*BM/nsub, (sub+1)*BM/nsub) of the tile
+    g.row_begin += tl.sub * (BM / tl.nsub);
+    int rows = g.row_end - g.row_begin;  // may exceed the tile (clamped by the row guards below)
+    if (rows <= 0) return;
+    if (tl.nsub > 1 && rows > BM / tl.nsub) rows = BM / tl.nsub;
     const bool short_tile = rows <= LM;        // workgroup-uniform
 
     // ---- copy roles: one copy instruction fills 8 tile rows (1024 bytes); lane l lands on
@@ -408,7 +412,7 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
     const int ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
-    const int64_t grid = xcd_grouped_grid(mtiles, ntn);
+    const int64_t grid = xcd_grouped_grid(mtiles, ntn, true);
     if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (pass == 0)
         ffn_bf16_dma_kernel<0, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(

@@ -80,6 +80,7 @@ __device__ __forceinline__ int swz_key(int row) { return ((row >> 1) & 7) ^ ((ro
 
 struct TileId {
     int mt, nt;
+    int sub, nsub;  // the tile's rows are cut into nsub equal parts and this workgroup owns part sub
     bool valid;
 };
 
@@ -88,17 +89,42 @@ struct TileId {
 // near-square block of tiles and re-use each other's A and B k-slices out of that XCD's
 // L2.  Each XCD (workgroup id mod 8) gets one contiguous range of tile numbers, so an
 // expert's weights are mostly streamed by one XCD.
+//
+// With SPLIT_TAIL, the tiles an XCD has left after its last full round of 32 (one per CU)
+// are cut along M into 2 or 4 row parts, each its own workgroup, so that the last round
+// occupies the CUs that would idle; the parts are dispatched last because workgroups are
+// handed out in id order.
 constexpr int TILE_GM = 4;
+constexpr int CUS_PER_XCD = 32;
 
+template <bool SPLIT_TAIL>
 __device__ __forceinline__ TileId xcd_grouped_tile(int total_mtiles, int ntn) {
     TileId t;
     t.valid = false;
-    t.mt = t.nt = 0;
+    t.mt = t.nt = t.sub = 0;
+    t.nsub = 1;
     const int total = total_mtiles * ntn;
     const int per_xcd = (total + 7) / 8;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int tile = xcd * per_xcd + slot;
-    if (slot >= per_xcd || tile >= total) return t;
+    const int first = xcd * per_xcd;
+    int cnt = total - first;
+    cnt = cnt > per_xcd ? per_xcd : cnt;
+    if (cnt <= 0) return t;
+    int idx = slot;
+    if (SPLIT_TAIL) {
+        const int full = cnt / CUS_PER_XCD * CUS_PER_XCD, r = cnt - full;
+        const int s = r == 0 ? 1 : (r * 4 <= CUS_PER_XCD ? 4 : (r * 2 <= CUS_PER_XCD ? 2 : 1));
+        if (slot >= full) {
+            const int q = slot - full;
+            if (q >= r * s) return t;
+            idx = full + q / s;
+            t.sub = q % s;
+            t.nsub = s;
+        }
+    } else if (slot >= cnt) {
+        return t;
+    }
+    const int tile = first + idx;
     const int grp = tile / (TILE_GM * ntn);
     const int first_m = grp * TILE_GM;
     const int gsz = total_mtiles - first_m < TILE_GM ? total_mtiles - first_m : TILE_GM;
@@ -109,9 +135,11 @@ __device__ __forceinline__ TileId xcd_grouped_tile(int total_mtiles, int ntn) {
     return t;
 }
 
-// Host side: workgroups to launch (a multiple of 8 that covers every tile).
-static inline int64_t xcd_grouped_grid(int64_t mtiles_bound, int ntn) {
-    return (mtiles_bound * ntn + 7) / 8 * 8;
+// Host side: workgroups to launch (a multiple of 8 that covers every tile, plus room for a
+// split last round: at most CUS_PER_XCD workgroups per XCD replace its r < 32 tail tiles).
+static inline int64_t xcd_grouped_grid(int64_t mtiles_bound, int ntn, bool split_tail) {
+    const int64_t per_xcd = (mtiles_bound * ntn + 7) / 8;
+    return (per_xcd + (split_tail ? CUS_PER_XCD : 0)) * 8;
 }
 
 }  // namespace c2r
