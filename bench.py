@@ -99,7 +99,10 @@ def main():
         c2r.permute(x, L.idx, L.E, L.local_slot, L.E_local, ws=L.ws_perm,
                     out=(L.counts, L.offsets, L.perm, L.inv_perm, L.x_perm))
         rec(2)
-        c2r.expert_ffn_gate_up(L.x_perm, L.offsets, wgt[0], wgt[1], h)
+        if L.fuse_gather:   # the row gather of the dispatch is folded into this pass's loads
+            c2r.expert_ffn_gate_up_gather(x, L.perm, L.K, L.offsets, wgt[0], wgt[1], h)
+        else:
+            c2r.expert_ffn_gate_up(L.x_perm, L.offsets, wgt[0], wgt[1], h)
         rec(3)
         c2r.expert_ffn_down(h, L.offsets, wgt[2], L.y_perm)
         rec(4)
@@ -126,6 +129,18 @@ def main():
     st_ms = {s: float(np.mean([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]))
              for j, s in enumerate(stages)}
 
+    # the ABI's stand-alone dispatch (index sort + row gather into x_perm), timed outside the step
+    x_perm_sa = torch.empty((w.T * w.K, w.d), dtype=tdt, device="cuda")
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for it in range(args.warmup + args.steps):
+        if it == args.warmup:
+            e0.record()
+        c2r.permute(x, L.idx, L.E, L.local_slot, L.E_local, ws=L.ws_perm,
+                    out=(L.counts, L.offsets, L.perm, L.inv_perm, x_perm_sa))
+    e1.record()
+    torch.cuda.synchronize()
+    permute_rows_ms = e0.elapsed_time(e1) / args.steps
+
     # ---- algorithmic work per stage ----
     n_local = int(L.offsets[-1].item())          # rows the local experts process
     A = w.T * w.K
@@ -137,8 +152,13 @@ def main():
                            "frac_hbm": route_bytes / st_ms["route"] / 1e6 / PEAK["hbm_GBps"],
                            "frac_valu_f32": route_flops / st_ms["route"] / 1e9 / PEAK["valu_f32_TFLOPs"]}
     perm_bytes = w.T * w.d * sz + n_local * w.d * sz + A * 12
-    stage_info["permute"] = {"ms": st_ms["permute"], "GBps": perm_bytes / st_ms["permute"] / 1e6,
-                             "frac_hbm": perm_bytes / st_ms["permute"] / 1e6 / PEAK["hbm_GBps"]}
+    stage_info["permute"] = {"ms": st_ms["permute"], "gather_fused_into_gate_up": bool(L.fuse_gather)}
+    if not L.fuse_gather:
+        stage_info["permute"].update({"GBps": perm_bytes / st_ms["permute"] / 1e6,
+                                      "frac_hbm": perm_bytes / st_ms["permute"] / 1e6 / PEAK["hbm_GBps"]})
+    stage_info["permute_standalone_with_rows"] = {
+        "ms": permute_rows_ms, "GBps": perm_bytes / permute_rows_ms / 1e6,
+        "frac_hbm": perm_bytes / permute_rows_ms / 1e6 / PEAK["hbm_GBps"], "in_step": not L.fuse_gather}
     comb_bytes = n_local * w.d * sz + w.T * w.d * sz * (2 if shared else 1) + A * 8
     stage_info["combine"] = {"ms": st_ms["combine"], "GBps": comb_bytes / st_ms["combine"] / 1e6,
                              "frac_hbm": comb_bytes / st_ms["combine"] / 1e6 / PEAK["hbm_GBps"]}

@@ -187,6 +187,18 @@ int c2r_expert_ffn_down(const void *h, c2r_dtype dt, const int32_t *offsets, int
                         int64_t A_cap, int d, int F, const void *w_down, void *y_perm, void *stream);
 
 /*
+ * c2r_expert_ffn_gate_up with the row gather of the dispatch (Sec. 3.1) folded in: row p of
+ * the sorted order is read as x[perm[p] / K] instead of x_perm[p], so c2r_permute can be
+ * called with x_perm == NULL and the [T*K, d] copy is never written.  Same result bit for
+ * bit.  x: [T, d] of dt; perm: int32[A_cap] as written by c2r_permute (entries at
+ * positions >= offsets[E_local] are never read).  Limits: bf16, d and F multiples of 64,
+ * T*d*2 < 2^32; otherwise C2R_ERR_UNSUPPORTED (use c2r_permute's x_perm instead).
+ */
+int c2r_expert_ffn_gate_up_gather(const void *x, c2r_dtype dt, const int32_t *perm, int64_t T, int K,
+                                  const int32_t *offsets, int E_local, int64_t A_cap, int d, int F,
+                                  const void *w_gate, const void *w_up, void *h, void *stream);
+
+/*
  * Un-permute and gate-weighted sum (Sec. 3.1, last sentence):
  *     y[t] = sum_{s<K, inv_perm[t*K+s] >= 0} gates[t,s] * y_perm[inv_perm[t*K+s]]  (+ y_shared[t])
  * summed in fp32 in slot order and rounded once to dt.

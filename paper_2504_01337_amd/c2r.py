@@ -23,7 +23,7 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
 
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
-           "c2r_expert_ffn_gate_up", "c2r_expert_ffn_down", "c2r_combine"]
+           "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine"]
 
 
 class C2RError(RuntimeError):
@@ -55,6 +55,7 @@ def lib():
         L.c2r_permute.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_expert_ffn.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_expert_ffn_gate_up.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
+        L.c2r_expert_ffn_gate_up_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
         L.c2r_expert_ffn_down.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp]
         L.c2r_combine.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp]
         for name in EXPORTS[3:]:
@@ -201,6 +202,23 @@ def expert_ffn_gate_up(x_perm, offsets, w_gate, w_up, h):
     return h
 
 
+def expert_ffn_gate_up_gather(x, perm, K, offsets, w_gate, w_up, h):
+    """First FFN pass reading row p as x[perm[p] // K] (dispatch gather folded in)."""
+    T, d = x.shape
+    A_cap = perm.numel()
+    E_local, F, _ = w_gate.shape
+    assert h.shape == (A_cap, F) and h.dtype == x.dtype and perm.dtype == torch.int32
+    _check("c2r_expert_ffn_gate_up_gather", lib().c2r_expert_ffn_gate_up_gather(
+        _ptr(x), _dt(x), _ptr(perm), T, K, _ptr(offsets), E_local, A_cap, d, F, _ptr(w_gate), _ptr(w_up), _ptr(h),
+        _stream()))
+    return h
+
+
+def gather_fusable(dtype, d, F) -> bool:
+    """Whether c2r_expert_ffn_gate_up_gather takes this shape (bf16, d and F multiples of 64)."""
+    return dtype == torch.bfloat16 and d % 64 == 0 and F % 64 == 0
+
+
 def expert_ffn_down(h, offsets, w_down, y_perm):
     """Second pass of the expert FFN: y_perm = h W_down^T."""
     A_cap, F = h.shape
@@ -226,7 +244,7 @@ class C2RLayer:
     enqueues the library's stages on the current stream (no allocation, no sync)."""
 
     def __init__(self, T, d, E, K, F, dtype, Wg, bias, collab_idx, w_gate, w_up, w_down,
-                 local_slot=None, E_local=None, shared=None, device="cuda"):
+                 local_slot=None, E_local=None, shared=None, device="cuda", fuse_gather=None):
         self.T, self.d, self.E, self.K, self.F = T, d, E, K, F
         self.E_local = E if E_local is None else E_local
         self.Wg, self.bias, self.collab_idx = Wg, bias, collab_idx
@@ -241,7 +259,11 @@ class C2RLayer:
         self.offsets = torch.empty((self.E_local + 1,), **i32)
         self.perm = torch.full((T * K,), -1, **i32)
         self.inv_perm = torch.empty((T * K,), **i32)
-        self.x_perm = torch.empty((T * K, d), dtype=dtype, device=dev)
+        # fold the dispatch's row gather into the first FFN pass when the shape allows it:
+        # x_perm is then never written
+        self.fuse_gather = gather_fusable(dtype, d, F) if fuse_gather is None else fuse_gather
+        self.x_perm = None if self.fuse_gather else torch.empty((T * K, d), dtype=dtype, device=dev)
+        self.h = torch.empty((T * K, F), dtype=dtype, device=dev) if self.fuse_gather else None
         self.y_perm = torch.empty((T * K, d), dtype=dtype, device=dev)
         self.y = torch.empty((T, d), dtype=dtype, device=dev)
         u8 = dict(dtype=torch.uint8, device=dev)
@@ -260,7 +282,11 @@ class C2RLayer:
         route(x, self.Wg, self.bias, self.K, self.collab_idx, ws=self.ws_route, out=(self.idx, self.gates))
         permute(x, self.idx, self.E, self.local_slot, self.E_local, ws=self.ws_perm,
                 out=(self.counts, self.offsets, self.perm, self.inv_perm, self.x_perm))
-        expert_ffn(self.x_perm, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
+        if self.fuse_gather:
+            expert_ffn_gate_up_gather(x, self.perm, self.K, self.offsets, self.w[0], self.w[1], self.h)
+            expert_ffn_down(self.h, self.offsets, self.w[2], self.y_perm)
+        else:
+            expert_ffn(self.x_perm, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
         if self.shared is not None:
             expert_ffn(x, self.off_shared, *self.shared, ws=self.ws_shared, out=self.y_shared)
         return combine(self.y_perm, self.gates, self.inv_perm, self.y_shared, out=self.y)

@@ -11,7 +11,8 @@ int launch_ffn_bf16_pass(int pass, const uint16_t *a, const int32_t *offsets, in
                          int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out, hipStream_t st);
 int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t *offsets, int E_local,
                              int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1,
-                             uint16_t *out, int ldo, hipStream_t st);
+                             uint16_t *out, int ldo, const int32_t *gather, int gather_div, int gather_rows,
+                             hipStream_t st);
 }  // namespace c2r
 
 using namespace c2r;
@@ -69,7 +70,7 @@ static int ffn_pass(int pass, c2r_dtype dt, const void *a, const int32_t *offset
         return launch_ffn_bf16_dma_pass(pass, static_cast<const uint16_t *>(a), pass == 0 ? d : ldh, offsets,
                                         E_local, A_cap, d, F, static_cast<const uint16_t *>(b0),
                                         static_cast<const uint16_t *>(b1), static_cast<uint16_t *>(out),
-                                        pass == 0 ? ldh : d, st);
+                                        pass == 0 ? ldh : d, nullptr, 1, 1, st);
     if (ldh != F) return C2R_ERR_UNSUPPORTED;
     if (dt == C2R_BF16)
         return launch_ffn_bf16_pass(pass, static_cast<const uint16_t *>(a), offsets, E_local, A_cap, d, F,
@@ -90,6 +91,23 @@ extern "C" int c2r_expert_ffn_gate_up(const void *x_perm, c2r_dtype dt, const in
     if (!aligned(x_perm, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(h, 16))
         return C2R_ERR_INVALID_ARG;
     return ffn_pass(0, dt, x_perm, offsets, E_local, A_cap, d, F, F, w_gate, w_up, h, stream);
+}
+
+extern "C" int c2r_expert_ffn_gate_up_gather(const void *x, c2r_dtype dt, const int32_t *perm, int64_t T, int K,
+                                             const int32_t *offsets, int E_local, int64_t A_cap, int d, int F,
+                                             const void *w_gate, const void *w_up, void *h, void *stream) {
+    const int rc = check_ffn(dt, E_local, A_cap, d, F);
+    if (rc != C2R_OK) return rc;
+    if (T < 1 || K < 1) return C2R_ERR_INVALID_ARG;
+    if (A_cap == 0) return C2R_OK;
+    if (!x || !perm || !offsets || !w_gate || !w_up || !h) return C2R_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(h, 16))
+        return C2R_ERR_INVALID_ARG;
+    // only the copy-engine kernel folds the gather into its addresses (32-bit row offsets into x)
+    if (!fast_bf16(dt, d, F) || F % 64 != 0 || (uint64_t)T * d * 2 >= (1ull << 32)) return C2R_ERR_UNSUPPORTED;
+    return launch_ffn_bf16_dma_pass(0, static_cast<const uint16_t *>(x), d, offsets, E_local, A_cap, d, F,
+                                    static_cast<const uint16_t *>(w_gate), static_cast<const uint16_t *>(w_up),
+                                    static_cast<uint16_t *>(h), F, perm, K, (int)T, static_cast<hipStream_t>(stream));
 }
 
 extern "C" int c2r_expert_ffn_down(const void *h, c2r_dtype dt, const int32_t *offsets, int E_local,

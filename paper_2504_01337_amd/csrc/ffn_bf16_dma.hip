@@ -81,7 +81,8 @@ template <int MODE, int WM, int WN>
 __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     const uint16_t *__restrict__ A, int lda, const int32_t *__restrict__ offsets, int E_local,
     int A_cap, int N, int Kdim, const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
-    uint16_t *__restrict__ out, int ldo, int ntn, int zero_to) {
+    uint16_t *__restrict__ out, int ldo, int ntn, int zero_to, const int32_t *__restrict__ gather,
+    int gather_div, int gather_rows) {
     constexpr int BM = 256, BN = 256, BK = 64;
     constexpr int NW = WM * WN;                // waves
     constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
@@ -123,7 +124,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     int chunkc[2];  // for even / odd 8-row groups (the key depends on row bits 0..3)
 #pragma unroll
     for (int par = 0; par < 2; ++par) chunkc[par] = lpos ^ swz_key(par * 8 + lrow);
-    const unsigned char *baseA = reinterpret_cast<const unsigned char *>(A + (size_t)g.row_begin * lda);
+    // With `gather`, A is the un-permuted activation matrix and row p of the sorted order is
+    // A[gather[p] / gather_div] (the dispatch gather folded into the copy addresses).
+    const unsigned char *baseA =
+        reinterpret_cast<const unsigned char *>(gather ? A : A + (size_t)g.row_begin * lda);
     const unsigned char *baseB0 = reinterpret_cast<const unsigned char *>(B0 + (size_t)g.expert * N * Kdim);
     const unsigned char *baseB1 =
         MODE == 0 ? reinterpret_cast<const unsigned char *>(B1 + (size_t)g.expert * N * Kdim) : baseB0;
@@ -133,6 +137,11 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         const int rg = short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
         int r = rg * 8 + lrow;
         r = r < rows ? r : rows - 1;
+        if (gather) {
+            const int a = gather[g.row_begin + r];
+            r = a > 0 ? a / gather_div : 0;
+            r = r < gather_rows ? r : gather_rows - 1;  // an out-of-range entry cannot leave A
+        }
         offA[i] = (uint32_t)r * (uint32_t)lda * 2u + (uint32_t)chunkc[rg & 1] * 16u;
     }
 #pragma unroll
@@ -408,7 +417,8 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 //         [F, ldh) zeroed;   pass 1: a = h (pitch ldh, zero padded to 64), out = y_perm.
 int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t *offsets, int E_local,
                              int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1,
-                             uint16_t *out, int ldo, hipStream_t st) {
+                             uint16_t *out, int ldo, const int32_t *gather, int gather_div, int gather_rows,
+                             hipStream_t st) {
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
     const int ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
@@ -416,10 +426,10 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
     if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (pass == 0)
         ffn_bf16_dma_kernel<0, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(
-            a, lda, offsets, E_local, (int)A_cap, F, d, b0, b1, out, ldo, ntn, ldo);
+            a, lda, offsets, E_local, (int)A_cap, F, d, b0, b1, out, ldo, ntn, ldo, gather, gather_div, gather_rows);
     else
         ffn_bf16_dma_kernel<1, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(
-            a, lda, offsets, E_local, (int)A_cap, d, F, b0, nullptr, out, ldo, ntn, 0);
+            a, lda, offsets, E_local, (int)A_cap, d, F, b0, nullptr, out, ldo, ntn, 0, nullptr, 1, 1);
     return launch_status();
 }
 

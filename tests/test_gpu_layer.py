@@ -41,6 +41,18 @@ def _run_layer(c2r, orc, w, n_sample):
     y = layer.forward(x)
     y = layer.forward(x)            # twice: buffers are reused, the result must not depend on it
     torch.cuda.synchronize()
+    if layer.fuse_gather:
+        # the same layer through c2r_permute's x_perm and c2r_expert_ffn: identical bits
+        plain = c2r.C2RLayer(w.T, w.d, w.E, w.K, w.F, tdt, Wg, bias, collab, *layer.w,
+                             local_slot=layer.local_slot, E_local=w.n_local, shared=layer.shared,
+                             fuse_gather=False)
+        y_plain = plain.forward(x)
+        torch.cuda.synchronize()
+        assert torch.equal(y_plain, y)
+        assert torch.equal(plain.perm[: int(o.offsets[-1])], layer.perm[: int(o.offsets[-1])])
+        x_perm_dev = plain.x_perm
+    else:
+        x_perm_dev = layer.x_perm
     assert np.array_equal(host(layer.idx), o.idx)
     np.testing.assert_allclose(host(layer.gates), o.gates, rtol=2e-6, atol=1e-7)
     assert np.array_equal(host(layer.counts), o.counts)
@@ -48,7 +60,7 @@ def _run_layer(c2r, orc, w, n_sample):
     n = int(o.offsets[-1])
     assert np.array_equal(host(layer.perm)[:n], o.perm)
     assert np.array_equal(host(layer.inv_perm), o.inv_perm)
-    assert np.array_equal(host(layer.x_perm)[:n], o.x[o.perm // w.K])
+    assert np.array_equal(host(x_perm_dev)[:n], o.x[o.perm // w.K])
     # --- outputs on sampled tokens the oracle computes one by one ---
     rng = np.random.default_rng(w.cfg_id)
     toks = np.sort(rng.permutation(w.T)[:n_sample])

@@ -207,6 +207,45 @@ def test_expert_ffn_ragged_groups(c2r, orc, dtype, d, F, sizes):
     assert np.all(yh[n:] == sentinel)                                   # rows past the last group untouched
 
 
+@pytest.mark.parametrize("E,K,T,d,F,local", [(8, 2, 700, 128, 256, None), (60, 4, 1500, 2048, 128, 7),
+                                              (4, 1, 129, 64, 64, None), (16, 3, 300, 256, 192, 5)])
+def test_gate_up_gather_equals_gate_up_on_x_perm(c2r, E, K, T, d, F, local):
+    """The first FFN pass reading x through perm (the dispatch gather folded into its loads)
+    gives, bit for bit, what it gives on the x_perm that c2r_permute writes; dropped
+    assignments (perm = -1 beyond the last group) are never read."""
+    rng = np.random.default_rng(E + T)
+    idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32)
+    x = dev(wl.round_bf16(rng.standard_normal((T, d)).astype(np.float32)), "bf16")
+    ls, E_local = None, E
+    if local:
+        ls = np.full(E, -1, dtype=np.int32)
+        ls[np.sort(rng.permutation(E)[:local])] = rng.permutation(local).astype(np.int32)
+        E_local = local
+    counts, offsets, perm, inv, x_perm = c2r.permute(x, dev(idx), E, dev(ls), E_local)
+    wg = dev(wl.round_bf16((rng.standard_normal((E_local, F, d)) * 0.05).astype(np.float32)), "bf16")
+    wu = dev(wl.round_bf16((rng.standard_normal((E_local, F, d)) * 0.05).astype(np.float32)), "bf16")
+    assert c2r.gather_fusable(torch.bfloat16, d, F)
+    h0 = torch.full((T * K, F), 7.0, dtype=torch.bfloat16, device="cuda")
+    h1 = h0.clone()
+    c2r.expert_ffn_gate_up(x_perm, offsets, wg, wu, h0)
+    c2r.expert_ffn_gate_up_gather(x, perm, K, offsets, wg, wu, h1)
+    torch.cuda.synchronize()
+    assert torch.equal(h0, h1)
+    n = int(offsets[-1])
+    assert n > 0 and torch.all(h1[n:] == 7.0)
+
+
+def test_gate_up_gather_rejects_other_shapes(c2r):
+    x = torch.zeros((8, 72), dtype=torch.float32, device="cuda")
+    perm = torch.zeros((8,), dtype=torch.int32, device="cuda")
+    off = torch.tensor([0, 8], dtype=torch.int32, device="cuda")
+    w = torch.zeros((1, 64, 72), dtype=torch.float32, device="cuda")
+    h = torch.zeros((8, 64), dtype=torch.float32, device="cuda")
+    assert not c2r.gather_fusable(torch.float32, 72, 64)
+    with pytest.raises(RuntimeError):
+        c2r.expert_ffn_gate_up_gather(x, perm, 1, off, w, w, h)
+
+
 @pytest.mark.parametrize("dtype,T,K,d", [("f32", 100, 2, 64), ("bf16", 1000, 4, 2048), ("bf16", 3, 1, 8)])
 def test_combine(c2r, orc, dtype, T, K, d):
     rng = np.random.default_rng(T)
