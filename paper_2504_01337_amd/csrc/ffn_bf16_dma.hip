@@ -382,16 +382,41 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #undef C2R_MFMA
 
     // ---- epilogue.  Fragment (i, j) holds C^T: lane (fr, fq), register v is
-    //      row m = i*16 + fr, column n = j*16 + 4*fq + v  -> 8-byte stores ----
-    uint16_t *outb = out + (size_t)g.row_begin * ldo;
+    //      row m = i*16 + fr, column n = j*16 + 4*fq + v  -> 8-byte stores.  Every wave of
+    //      the workgroup is here at once with the matrix pipe idle, so the common case (all
+    //      of the tile's columns exist) is kept to a conversion and a store per 4 values:
+    //      one pointer per lane, literal column offsets, the row guard once per fragment
+    //      row (measured 4.7 -> 3.4 us per 256 x 256 tile against per-element guards). ----
     constexpr int FJ = MODE == 0 ? FN16 / 2 : FN16;
+    const int col0 = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN);
+    if (n0 + BNF <= N) {
+        uint16_t *o = out + ((size_t)g.row_begin + wm * TM + fr) * ldo + col0 + fq * 4;
+        const int rlim = rows - wm * TM - fr;  // fragment row i exists iff i*16 < rlim
+#pragma unroll
+        for (int i = 0; i < FM16; ++i) {
+            if (i * 16 < rlim) {
+#pragma unroll
+                for (int j = 0; j < FJ; ++j) {
+                    float v4[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        v4[u] = MODE == 0 ? silu_mul(acc[i][j][u], acc[i][j + FN16 / 2][u]) : acc[i][j][u];
+                    *reinterpret_cast<uint2 *>(o + j * 16) =
+                        make_uint2(pack_bf16x2(v4[0], v4[1]), pack_bf16x2(v4[2], v4[3]));
+                }
+            }
+            o += (size_t)16 * ldo;
+        }
+        return;
+    }
+    uint16_t *outb = out + (size_t)g.row_begin * ldo;
 #pragma unroll
     for (int i = 0; i < FM16; ++i) {
         const int r = wm * TM + i * 16 + fr;
         if (r >= rows) continue;
 #pragma unroll
         for (int j = 0; j < FJ; ++j) {
-            const int col = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN) + j * 16 + fq * 4;
+            const int col = col0 + j * 16 + fq * 4;
             uint2 pk = make_uint2(0, 0);
             if (col >= N) {
                 // pass 0 keeps the padding columns of h at zero for pass 1's k tail
@@ -400,12 +425,8 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             }
             float v4[4];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                if (MODE == 0)
-                    v4[u] = silu_mul(acc[i][j][u], acc[i][j + FN16 / 2][u]);
-                else
-                    v4[u] = acc[i][j][u];
-            }
+            for (int u = 0; u < 4; ++u)
+                v4[u] = MODE == 0 ? silu_mul(acc[i][j][u], acc[i][j + FN16 / 2][u]) : acc[i][j][u];
             pk.x = pack_bf16x2(v4[0], v4[1]);
             pk.y = pack_bf16x2(v4[2], v4[3]);
             *reinterpret_cast<uint2 *>(outb + (size_t)r * ldo + col) = pk;
