@@ -241,10 +241,18 @@ def combine(y_perm, gates, inv_perm, y_shared=None, out=None):
 
 class C2RLayer:
     """One C2R MoE layer with all buffers allocated up front: forward() only
-    enqueues the library's stages on the current stream (no allocation, no sync)."""
+    enqueues the library's stages (no allocation, no host synchronisation).
+
+    overlap=True (needs a shared always-on expert) spreads the work over two streams of
+    default priority, because the shared expert needs neither the routing nor the dispatch:
+        side stream : shared gate/up ........................ shared down
+        main stream : route, permute | routed gate/up | routed down | combine
+    Measured at the Qwen-MoE shape this is worth about 1 % of the step (the router's fp32
+    FMAs and the GEMM's MFMAs share the SIMDs' issue slots, so what route and permute
+    save, the shared gate/up pass beside them loses again); the default is one stream."""
 
     def __init__(self, T, d, E, K, F, dtype, Wg, bias, collab_idx, w_gate, w_up, w_down,
-                 local_slot=None, E_local=None, shared=None, device="cuda", fuse_gather=None):
+                 local_slot=None, E_local=None, shared=None, device="cuda", fuse_gather=None, overlap=False):
         self.T, self.d, self.E, self.K, self.F = T, d, E, K, F
         self.E_local = E if E_local is None else E_local
         self.Wg, self.bias, self.collab_idx = Wg, bias, collab_idx
@@ -263,30 +271,92 @@ class C2RLayer:
         # x_perm is then never written
         self.fuse_gather = gather_fusable(dtype, d, F) if fuse_gather is None else fuse_gather
         self.x_perm = None if self.fuse_gather else torch.empty((T * K, d), dtype=dtype, device=dev)
+        # the two FFN passes are enqueued as calls of their own when h needs no padded pitch
+        # (then the layer owns h); otherwise c2r_expert_ffn runs both out of its workspace
         self.h = torch.empty((T * K, F), dtype=dtype, device=dev) if self.fuse_gather else None
         self.y_perm = torch.empty((T * K, d), dtype=dtype, device=dev)
         self.y = torch.empty((T, d), dtype=dtype, device=dev)
         u8 = dict(dtype=torch.uint8, device=dev)
         self.ws_route = torch.empty(max(256, workspace_bytes(STAGE_ROUTE, T, d, E, K, 0, dt)), **u8)
         self.ws_perm = torch.empty(max(256, workspace_bytes(STAGE_PERMUTE, T, d, E, K, 0, dt)), **u8)
-        self.ws_ffn = torch.empty(max(256, workspace_bytes(STAGE_EXPERT_FFN, T * K, d, self.E_local, 1, F, dt)), **u8)
+        if not self.fuse_gather:
+            self.ws_ffn = torch.empty(max(256, workspace_bytes(STAGE_EXPERT_FFN, T * K, d, self.E_local, 1, F, dt)), **u8)
+        self.overlap = bool(overlap) and shared is not None
         if shared is not None:
             Fs = shared[0].shape[1]
             self.off_shared = torch.tensor([0, T], **i32)
+            self.split_shared = gather_fusable(dtype, d, Fs)
+            if self.split_shared:
+                self.h_shared = torch.empty((T, Fs), dtype=dtype, device=dev)
+            else:
+                self.ws_shared = torch.empty(max(256, workspace_bytes(STAGE_EXPERT_FFN, T, d, 1, 1, Fs, dt)), **u8)
             self.y_shared = torch.empty((T, d), dtype=dtype, device=dev)
-            self.ws_shared = torch.empty(max(256, workspace_bytes(STAGE_EXPERT_FFN, T, d, 1, 1, Fs, dt)), **u8)
         else:
             self.y_shared = None
+        if self.overlap:
+            self.side = torch.cuda.Stream(device=dev)          # default priority
+            self.ev = {k: torch.cuda.Event() for k in ("x", "shared_gate_up", "gate_up", "shared_down")}
 
-    def forward(self, x):
-        route(x, self.Wg, self.bias, self.K, self.collab_idx, ws=self.ws_route, out=(self.idx, self.gates))
-        permute(x, self.idx, self.E, self.local_slot, self.E_local, ws=self.ws_perm,
-                out=(self.counts, self.offsets, self.perm, self.inv_perm, self.x_perm))
-        if self.fuse_gather:
-            expert_ffn_gate_up_gather(x, self.perm, self.K, self.offsets, self.w[0], self.w[1], self.h)
-            expert_ffn_down(self.h, self.offsets, self.w[2], self.y_perm)
-        else:
-            expert_ffn(self.x_perm, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
+    # names of the stages forward() runs, in the order a trace lists them
+    STAGES = ("route", "permute", "ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down", "combine")
+
+    def forward(self, x, trace=None):
+        """y = layer(x).  trace: optional {stage: (start_event, end_event)}; each pair is
+        recorded on the stream its stage runs on (timing events, made by the caller)."""
+        main = torch.cuda.current_stream()
+        side = self.side if self.overlap else main
+
+        def run(name, stream, fn):
+            with torch.cuda.stream(stream):
+                if trace is not None:
+                    trace[name][0].record(stream)
+                fn()
+                if trace is not None:
+                    trace[name][1].record(stream)
+
+        def gate_up():
+            if self.fuse_gather:
+                expert_ffn_gate_up_gather(x, self.perm, self.K, self.offsets, self.w[0], self.w[1], self.h)
+            else:   # both passes
+                expert_ffn(self.x_perm, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
+
+        def down():
+            if self.fuse_gather:
+                expert_ffn_down(self.h, self.offsets, self.w[2], self.y_perm)
+
+        def shared_gate_up():
+            if self.split_shared:
+                expert_ffn_gate_up(x, self.off_shared, self.shared[0], self.shared[1], self.h_shared)
+            else:   # both passes
+                expert_ffn(x, self.off_shared, *self.shared, ws=self.ws_shared, out=self.y_shared)
+
+        def shared_down():
+            if self.split_shared:
+                expert_ffn_down(self.h_shared, self.off_shared, self.shared[2], self.y_shared)
+
+        if self.overlap:
+            self.ev["x"].record(main)                # x is ready, the previous call's combine has read y_shared
+            side.wait_event(self.ev["x"])
         if self.shared is not None:
-            expert_ffn(x, self.off_shared, *self.shared, ws=self.ws_shared, out=self.y_shared)
-        return combine(self.y_perm, self.gates, self.inv_perm, self.y_shared, out=self.y)
+            run("shared_gate_up", side, shared_gate_up)
+            if self.overlap:
+                self.ev["shared_gate_up"].record(side)
+        run("route", main, lambda: route(x, self.Wg, self.bias, self.K, self.collab_idx, ws=self.ws_route,
+                                         out=(self.idx, self.gates)))
+        run("permute", main, lambda: permute(x, self.idx, self.E, self.local_slot, self.E_local, ws=self.ws_perm,
+                                             out=(self.counts, self.offsets, self.perm, self.inv_perm, self.x_perm)))
+        if self.overlap:
+            main.wait_event(self.ev["shared_gate_up"])
+        run("ffn_gate_up", main, gate_up)
+        if self.overlap:
+            self.ev["gate_up"].record(main)
+            side.wait_event(self.ev["gate_up"])
+        if self.shared is not None:
+            run("shared_down", side, shared_down)
+            if self.overlap:
+                self.ev["shared_down"].record(side)
+        run("ffn_down", main, down)
+        if self.overlap:
+            main.wait_event(self.ev["shared_down"])
+        run("combine", main, lambda: combine(self.y_perm, self.gates, self.inv_perm, self.y_shared, out=self.y))
+        return self.y

@@ -42,10 +42,11 @@ def _run_layer(c2r, orc, w, n_sample):
     y = layer.forward(x)            # twice: buffers are reused, the result must not depend on it
     torch.cuda.synchronize()
     if layer.fuse_gather:
-        # the same layer through c2r_permute's x_perm and c2r_expert_ffn: identical bits
+        # the same layer through c2r_permute's x_perm and c2r_expert_ffn, and with the shared
+        # expert (if any) on a second stream: identical bits
         plain = c2r.C2RLayer(w.T, w.d, w.E, w.K, w.F, tdt, Wg, bias, collab, *layer.w,
                              local_slot=layer.local_slot, E_local=w.n_local, shared=layer.shared,
-                             fuse_gather=False)
+                             fuse_gather=False, overlap=True)
         y_plain = plain.forward(x)
         torch.cuda.synchronize()
         assert torch.equal(y_plain, y)
