@@ -105,17 +105,35 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    const GroupMap gmap = build_group_map<BM>(offsets, E_local, A_cap);
-    const TileId tl = xcd_grouped_tile<true>(gmap.total_mtiles, ntn);
-    if (!tl.valid) return;
-    GroupTile g = locate_group_tile(gmap, tl.mt, BM);
-    if (g.expert < 0) return;
-    const int n0 = tl.nt * BNF;
-    // a part of a split tail tile: rows [sub*BM/nsub, (sub+1)*BM/nsub) of the tile
-    g.row_begin += tl.sub * (BM / tl.nsub);
+    // Tile of this workgroup.  One group (a shared expert, a plain GEMM) needs no map: its
+    // bounds are two scalar loads and its tiles all cost the same.
+    GroupTile g;
+    int tile_nt, tile_nsub;
+    if (E_local == 1) {
+        int lo = offsets[0], hi = offsets[1];
+        lo = lo < 0 ? 0 : (lo > A_cap ? A_cap : lo);
+        hi = hi < lo ? lo : (hi > A_cap ? A_cap : hi);
+        const TileId t1 = xcd_grouped_tile<true>((hi - lo + BM - 1) / BM, ntn);
+        if (!t1.valid) return;
+        g.expert = 0;
+        g.row_begin = lo + t1.mt * BM + t1.sub * (BM / t1.nsub);  // of this workgroup's part of the tile
+        g.row_end = hi;
+        tile_nt = t1.nt;
+        tile_nsub = t1.nsub;
+    } else {
+        const RaggedMap rmap = build_ragged_map<BM>(offsets, E_local, A_cap);
+        const RaggedTile tr = ragged_tile<BM>(rmap, ntn, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
+        if (!tr.valid) return;
+        g.expert = tr.expert;
+        g.row_begin = tr.row_begin;
+        g.row_end = tr.row_end;
+        tile_nt = tr.nt;
+        tile_nsub = tr.nsub;
+    }
+    const int n0 = tile_nt * BNF;
     int rows = g.row_end - g.row_begin;  // may exceed the tile (clamped by the row guards below)
     if (rows <= 0) return;
-    if (tl.nsub > 1 && rows > BM / tl.nsub) rows = BM / tl.nsub;
+    if (tile_nsub > 1 && rows > BM / tile_nsub) rows = BM / tile_nsub;
     const bool short_tile = rows <= LM;        // workgroup-uniform
 
     // ---- copy roles: one copy instruction fills 8 tile rows (1024 bytes); lane l lands on
@@ -132,17 +150,26 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     const unsigned char *baseB1 =
         MODE == 0 ? reinterpret_cast<const unsigned char *>(B1 + (size_t)g.expert * N * Kdim) : baseB0;
     uint32_t offA[GA], offB[GB], rowB[GB];
+    int rowA[GA];
 #pragma unroll
     for (int i = 0; i < GA; ++i) {
         const int rg = short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
-        int r = rg * 8 + lrow;
-        r = r < rows ? r : rows - 1;
-        if (gather) {
-            const int a = gather[g.row_begin + r];
-            r = a > 0 ? a / gather_div : 0;
-            r = r < gather_rows ? r : gather_rows - 1;  // an out-of-range entry cannot leave A
+        const int r = rg * 8 + lrow;
+        rowA[i] = r < rows ? r : rows - 1;
+    }
+    if (gather) {
+#pragma unroll
+        for (int i = 0; i < GA; ++i) rowA[i] = gather[g.row_begin + rowA[i]];  // the index loads fly together
+#pragma unroll
+        for (int i = 0; i < GA; ++i) {
+            const int r = rowA[i] > 0 ? (int)((uint32_t)rowA[i] / (uint32_t)gather_div) : 0;
+            rowA[i] = r < gather_rows ? r : gather_rows - 1;  // an out-of-range entry cannot leave A
         }
-        offA[i] = (uint32_t)r * (uint32_t)lda * 2u + (uint32_t)chunkc[rg & 1] * 16u;
+    }
+#pragma unroll
+    for (int i = 0; i < GA; ++i) {
+        const int rg = short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
+        offA[i] = (uint32_t)rowA[i] * (uint32_t)lda * 2u + (uint32_t)chunkc[rg & 1] * 16u;
     }
 #pragma unroll
     for (int i = 0; i < GB; ++i) {
@@ -443,7 +470,7 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
     const int ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
-    const int64_t grid = xcd_grouped_grid(mtiles, ntn, true);
+    const int64_t grid = E_local == 1 ? xcd_grouped_grid(mtiles, ntn, true) : ragged_grid(mtiles, ntn);
     if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (pass == 0)
         ffn_bf16_dma_kernel<0, WM, WN><<<dim3((unsigned)grid), dim3(WM * WN * 64), 0, st>>>(

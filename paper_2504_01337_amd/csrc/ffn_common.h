@@ -142,4 +142,132 @@ static inline int64_t xcd_grouped_grid(int64_t mtiles_bound, int ntn, bool split
     return (per_xcd + (split_tail ? CUS_PER_XCD : 0)) * 8;
 }
 
+// ---- Ragged tile map of the fast bf16 kernel --------------------------------------------
+// Tiles are numbered expert after expert; inside an expert in chunks of TILE_GM M-tiles, and
+// inside a chunk N-tile after N-tile with the chunk's M-tiles fastest.  A chunk never spans
+// two experts, so the ~32 workgroups that run together on an XCD stream each expert's
+// weight k-slices once per chunk (with chunks of consecutive M-tiles regardless of expert,
+// a chunk held 2-3 small experts and streamed all of their weights: measured 2.2 x the
+// weight bytes at the Qwen-MoE shape).  Each XCD gets a contiguous range of tile numbers of
+// equal estimated COST, not equal count: an M-tile of at most BM/2 rows (only an expert's
+// last one can be) runs the short path at about half the time of a full one, and ranges of
+// equal count were measured 6 % apart in cost on Zipf-sized experts.  A boundary moves at
+// most 1/64 of the tiles away from its equal-count position, which bounds the workgroups a
+// launch needs (ragged_grid) without knowing the group sizes on the host.
+struct RaggedMap {
+    int lo, hi;        // this lane's expert: row range (clamped to [0, A_cap])
+    int tiles, first;  // its M-tiles and its first M-tile number
+    int cost, pcost;   // 2 per M-tile, 1 for a short last one; exclusive prefix over experts
+    int total_mtiles, total_cost;  // wave-uniform
+};
+
+template <int BM>
+__device__ __forceinline__ RaggedMap build_ragged_map(const int32_t *__restrict__ offsets, int E_local, int A_cap) {
+    const GroupMap gm = build_group_map<BM>(offsets, E_local, A_cap);
+    RaggedMap m;
+    m.lo = gm.lo;
+    m.hi = gm.hi;
+    m.tiles = gm.tiles;
+    m.first = gm.first;
+    m.total_mtiles = gm.total_mtiles;
+    const int cnt = gm.hi - gm.lo;
+    const bool short_last = gm.tiles > 0 && cnt - (gm.tiles - 1) * BM <= BM / 2;
+    m.cost = 2 * gm.tiles - (short_last ? 1 : 0);
+    const int lane = lane_id();
+    int incl = m.cost;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const int v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    m.pcost = incl - m.cost;
+    m.total_cost = __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
+    return m;
+}
+
+// First tile number of XCD x's range (x = 8: one past the last tile).  Same result in every
+// wave of the launch: integer arithmetic on the same map.
+__device__ __forceinline__ int ragged_boundary(const RaggedMap &m, int ntn, int x) {
+    const int total = m.total_mtiles * ntn;
+    if (x <= 0) return 0;
+    if (x >= 8) return total;
+    const int even = (int)((uint64_t)(uint32_t)total * (uint32_t)x / 8u), win = total / 64;
+    const uint64_t G = (uint64_t)(uint32_t)ntn * (uint32_t)m.total_cost;  // < 2^32 (launcher check)
+    const uint32_t g = (uint32_t)(G * (uint32_t)x / 8u);
+    const uint32_t clo = (uint32_t)ntn * (uint32_t)m.pcost, chi = clo + (uint32_t)ntn * (uint32_t)m.cost;
+    const uint64_t hit = __ballot(m.cost > 0 && g >= clo && g < chi);
+    if (hit == 0) return even;
+    const int e = __ffsll((unsigned long long)hit) - 1;
+    const int tiles = __builtin_amdgcn_readlane(m.tiles, e), first = __builtin_amdgcn_readlane(m.first, e);
+    const int cost = __builtin_amdgcn_readlane(m.cost, e), pc = __builtin_amdgcn_readlane(m.pcost, e);
+    const uint32_t r = g - (uint32_t)ntn * (uint32_t)pc;  // cost offset inside the expert
+    const int sh = 2 * tiles - cost;                       // 1: the last M-tile is short
+    const int gl = tiles - TILE_GM * ((tiles - 1) / TILE_GM);  // M-tiles of the last chunk
+    const uint32_t R = 2u * (uint32_t)(tiles - gl) * (uint32_t)ntn;  // cost of the full chunks
+    uint32_t t;
+    if (r < R)
+        t = r / 2u;
+    else  // the last chunk's tiles cost (2 gl - sh) / gl on average (its M-tiles alternate)
+        t = (uint32_t)(tiles - gl) * (uint32_t)ntn + (r - R) * (uint32_t)gl / (uint32_t)(2 * gl - sh);
+    const int b = first * ntn + (int)t;
+    return b < even - win ? even - win : (b > even + win ? even + win : b);
+}
+
+struct RaggedTile {
+    int expert, row_begin, row_end;  // row_begin: first row of the tile (part); row_end: the expert's end
+    int nt;
+    int sub, nsub;  // the tile's rows are cut into nsub equal parts and this workgroup owns part sub
+    bool valid;
+};
+
+// Workgroup (XCD, slot) -> tile.  The tiles an XCD has left after its last full round of
+// CUS_PER_XCD are cut along M into 2 or 4 row parts, each its own workgroup, so that the
+// last round occupies the CUs that would idle; the parts are dispatched last.
+template <int BM>
+__device__ __forceinline__ RaggedTile ragged_tile(const RaggedMap &m, int ntn, int xcd, int slot) {
+    RaggedTile t;
+    t.valid = false;
+    t.expert = -1;
+    t.row_begin = t.row_end = t.nt = t.sub = 0;
+    t.nsub = 1;
+    const int b0 = ragged_boundary(m, ntn, xcd), b1 = ragged_boundary(m, ntn, xcd + 1);
+    const int cnt = b1 - b0;
+    if (cnt <= 0) return t;
+    int idx = slot;
+    const int full = cnt / CUS_PER_XCD * CUS_PER_XCD, r = cnt - full;
+    const int s = r == 0 ? 1 : (r * 4 <= CUS_PER_XCD ? 4 : (r * 2 <= CUS_PER_XCD ? 2 : 1));
+    if (slot >= full) {
+        const int q = slot - full;
+        if (q >= r * s) return t;
+        idx = full + q / s;
+        t.sub = q % s;
+        t.nsub = s;
+    }
+    const int tile = b0 + idx;
+    const int tlo = m.first * ntn;
+    const uint64_t hit = __ballot(m.tiles > 0 && tile >= tlo && tile < tlo + m.tiles * ntn);
+    if (hit == 0) return t;
+    const int e = __ffsll((unsigned long long)hit) - 1;
+    const int tiles = __builtin_amdgcn_readlane(m.tiles, e), first = __builtin_amdgcn_readlane(m.first, e);
+    const int tp = tile - first * ntn;
+    const int c = tp / (TILE_GM * ntn);
+    const int gsz = tiles - c * TILE_GM < TILE_GM ? tiles - c * TILE_GM : TILE_GM;
+    const int rem = tp - c * TILE_GM * ntn;
+    const int mloc = c * TILE_GM + rem % gsz;
+    t.nt = rem / gsz;
+    t.expert = e;
+    t.row_begin = __builtin_amdgcn_readlane(m.lo, e) + mloc * BM + t.sub * (BM / t.nsub);
+    t.row_end = __builtin_amdgcn_readlane(m.hi, e);
+    t.valid = true;
+    return t;
+}
+
+// Host side: workgroups to launch for the ragged map: a range holds at most 1/8 + 2/64 of
+// the tiles (+1 for rounding), plus the split last round.
+static inline int64_t ragged_grid(int64_t mtiles_bound, int ntn) {
+    const int64_t total = mtiles_bound * ntn;
+    const int64_t per_xcd = (total + 7) / 8 + 2 * (total / 64) + 2;
+    return (per_xcd + CUS_PER_XCD) * 8;
+}
+
 }  // namespace c2r
