@@ -18,6 +18,8 @@
 // Contract (checked by the launcher): the contraction length seen by A is padded to a
 // multiple of 64 with zeros (lda >= 64 * ceil(K/64)); a B chunk past K is re-read from
 // chunk 0 of the same row and multiplied by those zeros.
+#include <type_traits>
+
 #include "ffn_common.h"
 
 namespace c2r {
@@ -191,13 +193,14 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     // unit takes one 64-lane x 16-byte request per ~16 cycles, so a burst of all of a
     // workgroup's copies would hold every wave at its copy instructions for ~1000 cycles
     // with the matrix pipe idle.
-    auto copy_piece = [&](int kt, unsigned char *stage, int p) {
+    // `inner`: kt is known not to be the last slice (no k tail to clamp).
+    auto copy_piece = [&](int kt, unsigned char *stage, int p, bool inner = false) {
         const uint32_t kb = (uint32_t)kt * ROWB;
         if (p < GA) {
             copy16_to_lds(baseA + offA[p] + kb, stage + (wave * GA + p) * 1024);
         } else {  // a B chunk past K is taken from chunk 0: it meets A's zero padding
             const int i = p - GA, rg = wave * GB + i;
-            const bool clampB = ktail && kt == nk - 1 && kt * BK + chunkc[rg & 1] * 8 >= Kdim;
+            const bool clampB = !inner && ktail && kt == nk - 1 && kt * BK + chunkc[rg & 1] * 8 >= Kdim;
             copy16_to_lds(baseB + (clampB ? rowB[i] : offB[i] + kb), stage + A_BYTES + rg * 1024);
         }
     };
@@ -260,7 +263,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #define C2R_COPY_IF(Q, NCP, CKT, CST, P0)           \
     if ((Q) < (NCP)) {                              \
         __builtin_amdgcn_sched_barrier(0);          \
-        copy_piece(CKT, CST, (P0) + (Q));           \
+        copy_piece(CKT, CST, (P0) + (Q), STEADY);   \
         __builtin_amdgcn_sched_barrier(0);          \
     }
 #define C2R_KSTEP(AS, BS, H, CKT, CST, P0, NCP)     \
@@ -284,7 +287,11 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     // none in the third so that they land before the next barrier), and the first fragments
     // of the next slice are read while the last k-step's MFMAs run, so the MFMA stream
     // never starts a slice by waiting on LDS.
-    auto slice_step = [&](int kt, unsigned char *cur, unsigned char *nxt) {
+    // `steady` (a compile-time flag): kt + 3 < nk, i.e. both following slices exist and neither
+    // is the last, so every copy is unconditional and unclamped: the instruction stream
+    // between the MFMAs is what limits a wave that has a SIMD nearly to itself.
+    auto slice_step = [&](int kt, unsigned char *cur, unsigned char *nxt, auto steady) {
+        constexpr bool STEADY = decltype(steady)::value;
 #ifndef C2R_CPA
 #define C2R_CPA 3
 #define C2R_CPB 3
@@ -292,8 +299,9 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #define C2R_CPD 0
 #endif
         static_assert(C2R_CPA + C2R_CPB + C2R_CPC + C2R_CPD == 8, "all pieces scheduled");
-        const bool c1 = kt + 1 < nk;
-        const int n1 = c1 ? C2R_CPB : 0, n1b = c1 ? C2R_CPC : 0, n1c = c1 ? C2R_CPD : 0, n2 = kt + 2 < nk ? C2R_CPA : 0;
+        const bool c1 = STEADY || kt + 1 < nk;
+        const int n1 = c1 ? C2R_CPB : 0, n1b = c1 ? C2R_CPC : 0, n1c = c1 ? C2R_CPD : 0;
+        const int n2 = STEADY || kt + 2 < nk ? C2R_CPA : 0;
         if (active) {
             read_a(cur, 0, 1, 1);
             C2R_KSTEP(0, 0, 0, kt + 1, nxt, C2R_CPA, n1);
@@ -314,7 +322,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         wait_copies_and_lds();  // my copies of slice kt+1 landed, my reads of `cur` returned
         lds_barrier();
         if (active) {
-            if (kt + 1 < nk) {
+            if (c1) {
                 read_a(nxt, 0, 0, 0);
                 read_b(nxt, 0, 0);
             }
@@ -396,10 +404,15 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             read_a(st0, 0, 0, 0);
             read_b(st0, 0, 0);
         }
-        for (int kt = 0; kt < nk; kt += 2) {
-            slice_step(kt, st0, st1);
+        int kt = 0;
+        for (; kt + 4 < nk; kt += 2) {  // both slices of the pair are followed by two inner slices
+            slice_step(kt, st0, st1, std::true_type{});
+            slice_step(kt + 1, st1, st0, std::true_type{});
+        }
+        for (; kt < nk; kt += 2) {
+            slice_step(kt, st0, st1, std::false_type{});
             if (kt + 1 >= nk) break;
-            slice_step(kt + 1, st1, st0);
+            slice_step(kt + 1, st1, st0, std::false_type{});
         }
         wait_copies_but<0>();
     }
