@@ -184,7 +184,11 @@ def test_permute(c2r, orc, E, K, T, d, dtype, local):
 @pytest.mark.parametrize("dtype,d,F,sizes", [
     ("f32", 64, 96, [5, 0, 70, 1, 130]), ("f32", 256, 512, [100, 300, 0, 3]),
     ("bf16", 128, 256, [300, 0, 1, 64, 257, 5]), ("bf16", 64, 88, [33, 700]),
-    ("bf16", 256, 688, [12, 0, 0, 513]), ("bf16", 2048, 128, [40, 260])])
+    ("bf16", 256, 688, [12, 0, 0, 513]), ("bf16", 2048, 128, [40, 260]),
+    # tile-map edges: group sizes around the 128-row short-tile and 256-row tile limits, groups of
+    # more than one 4-tile chunk, many small groups next to a large one, 64 groups
+    ("bf16", 64, 64, [128, 129, 127, 256, 255, 257, 0, 1]), ("bf16", 64, 128, [1100, 3, 0, 0, 2100, 64]),
+    ("bf16", 128, 64, [7] * 30 + [1500] + [0] * 20 + [130] * 13)])
 def test_expert_ffn_ragged_groups(c2r, orc, dtype, d, F, sizes):
     rng = np.random.default_rng(d + F)
     E = len(sizes)
