@@ -163,14 +163,20 @@ __device__ __forceinline__ void pick(const float (&l)[EP], uint64_t m, int &bi, 
     }
 }
 
+// ROWMAJOR (stored logits [T, E]): one wave per 64 tokens.  Otherwise (chunk partials):
+// SEL_WAVES waves per 64 tokens; each sums the chunks of a quarter of the experts (the
+// loads of one wave alone cover the memory latency four times worse) and leaves its
+// logits in LDS, then the first wave selects.
+constexpr int SEL_WAVES = 4;
+
 template <int EP, bool ROWMAJOR>
-__global__ __launch_bounds__(64) void route_select_kernel(
+__global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_kernel(
     const float *__restrict__ src, int nchunk, const float *__restrict__ bias,
     int64_t T, int E, int K, const int32_t *__restrict__ collab_idx, int Tc,
     int32_t *__restrict__ topk_idx, float *__restrict__ gates, float *__restrict__ logits_out) {
     __shared__ uint64_t mask_tab[C2R_MAX_E];
     constexpr int LP = EP + 1;  // odd pitch: per-lane row reads hit distinct banks
-    __shared__ float tile[ROWMAJOR ? 64 * LP : 1];
+    __shared__ float tile[64 * LP];
 
     const uint64_t all = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
     if (threadIdx.x < C2R_MAX_E) {
@@ -189,8 +195,8 @@ __global__ __launch_bounds__(64) void route_select_kernel(
         mask_tab[e] = m;
     }
 
-    const int64_t t = (int64_t)blockIdx.x * 64 + threadIdx.x;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t t = (int64_t)blockIdx.x * 64 + lane;
     float l[EP];
     if constexpr (ROWMAJOR) {
         // wave-private transpose: 64 consecutive rows of E floats are one contiguous run
@@ -222,20 +228,38 @@ __global__ __launch_bounds__(64) void route_select_kernel(
 #pragma unroll
         for (int e = 0; e < EP; ++e) l[e] = (e < E && lane < rows) ? tl[lane * LP + e] : 0.0f;
     } else {
-        const float *p = src + (size_t)blockIdx.x * nchunk * EP * 64 + lane;
+        static_assert(EP % SEL_WAVES == 0, "experts divide over the waves");
+        constexpr int EW = EP / SEL_WAVES;
+        const float *p = src + (size_t)blockIdx.x * nchunk * EP * 64 + (size_t)wave * EW * 64 + lane;
+        // chunk results are added left to right; four chunks are fetched at a time so that
+        // their loads are in flight together
+        constexpr int CU = 4;
+        float sum[EW];
+        for (int c0 = 0; c0 < nchunk; c0 += CU) {
+            float v[CU][EW];
 #pragma unroll
-        for (int e = 0; e < EP; ++e) l[e] = p[e * 64];
-        for (int c = 1; c < nchunk; ++c) {
-            p += EP * 64;
+            for (int u = 0; u < CU; ++u)
+                if (c0 + u < nchunk) {
 #pragma unroll
-            for (int e = 0; e < EP; ++e) l[e] = l[e] + p[e * 64];
+                    for (int j = 0; j < EW; ++j) v[u][j] = p[(size_t)(c0 + u) * EP * 64 + j * 64];
+                }
+#pragma unroll
+            for (int u = 0; u < CU; ++u)
+                if (c0 + u < nchunk) {
+#pragma unroll
+                    for (int j = 0; j < EW; ++j) sum[j] = (c0 + u == 0) ? v[u][j] : sum[j] + v[u][j];
+                }
         }
-        if (bias) {
 #pragma unroll
-            for (int e = 0; e < EP; ++e)
-                if (e < E) l[e] = l[e] + bias[e];
+        for (int j = 0; j < EW; ++j) {
+            const int e = wave * EW + j;
+            if (bias && e < E) sum[j] = sum[j] + bias[e];
+            tile[lane * LP + e] = sum[j];
         }
         __syncthreads();
+        if (wave != 0) return;
+#pragma unroll
+        for (int e = 0; e < EP; ++e) l[e] = tile[lane * LP + e];
     }
     if (t >= T) return;
 
@@ -379,7 +403,7 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
     }
 #undef C2R_ROUTE_TE
 #undef C2R_ROUTE_LAUNCH
-    C2R_EP_SWITCH(L.EP, route_select_kernel<EP, false><<<dim3((unsigned)ntiles), dim3(64), 0, st>>>(
+    C2R_EP_SWITCH(L.EP, route_select_kernel<EP, false><<<dim3((unsigned)ntiles), dim3(SEL_WAVES * 64), 0, st>>>(
                             part, L.nchunk, bias, T, E, K, collab_idx, Tc, topk_idx, gates, logits_out));
     return launch_status();
 }
