@@ -301,18 +301,20 @@ class C2RLayer:
     STAGES = ("route", "permute", "ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down", "combine")
 
     def forward(self, x, trace=None):
-        """y = layer(x).  trace: optional {stage: (start_event, end_event)}; each pair is
-        recorded on the stream its stage runs on (timing events, made by the caller)."""
+        """y = layer(x).  trace: optional {stage: (start_event, end_event)} for any subset of
+        STAGES; each pair is recorded on the stream its stage runs on (timing events, made by
+        the caller)."""
         main = torch.cuda.current_stream()
         side = self.side if self.overlap else main
 
         def run(name, stream, fn):
+            pair = trace.get(name) if trace is not None else None
             with torch.cuda.stream(stream):
-                if trace is not None:
-                    trace[name][0].record(stream)
+                if pair is not None:
+                    pair[0].record(stream)
                 fn()
-                if trace is not None:
-                    trace[name][1].record(stream)
+                if pair is not None:
+                    pair[1].record(stream)
 
         def gate_up():
             if self.fuse_gather:
