@@ -30,6 +30,10 @@ def main():
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0: skip)")
     ap.add_argument("--overlap", action="store_true",
                     help="run the shared expert on a second stream (stage spans then overlap)")
+    ap.add_argument("--isolate", action="store_true",
+                    help="also time every stage on its own with a 512 MiB cache-flushing write before each "
+                         "launch (the 256 MB memory-side cache otherwise serves back-to-back stages)")
+    ap.add_argument("--hash-inputs", action="store_true", help="add the SHA-256 of every generated host array")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device-to-device copies of known size (to scale rocprofv3's "
                          "FETCH_SIZE / WRITE_SIZE counters) and exit")
@@ -192,6 +196,61 @@ def main():
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["valu_f32_TFLOPs"], "traffic": None,
                     "avg_launch_ms": dom_ms, "launches_per_step": n_launch}
 
+    # ---- measured ceilings of this machine: matrix pipe (zeros / random operands) and a device copy ----
+    def measured_ceilings():
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        out_p = torch.empty(1024 * 512, dtype=torch.float32, device="cuda")
+        res = {}
+        g = torch.Generator(device="cpu").manual_seed(7)
+        for name, ops in (("mfma_bf16_zero_operands_TFLOPs", torch.zeros(1024 * 8, dtype=torch.bfloat16)),
+                          ("mfma_bf16_random_operands_TFLOPs",
+                           (torch.rand(1024 * 8, generator=g) * 2 - 1).to(torch.bfloat16))):
+            ops = ops.cuda()
+            c2r.probe_mfma_bf16(ops, 2000, 1024, out_p)
+            e0.record()
+            fl = c2r.probe_mfma_bf16(ops, 20000, 1024, out_p)
+            e1.record()
+            torch.cuda.synchronize()
+            res[name] = fl / e0.elapsed_time(e1) / 1e9
+        src = torch.full(((512 << 20) // 4,), 1.0, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        e0.record()
+        for _ in range(5):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        res["copy_read_plus_write_GBps"] = 5 * 2 * (512 << 20) / e0.elapsed_time(e1) / 1e6
+        return res
+
+    ceilings = measured_ceilings()
+
+    # ---- every stage on its own behind a cache flush ----
+    isolated = None
+    if args.isolate:
+        flush = torch.empty((512 << 20) // 4, dtype=torch.float32, device="cuda")
+        n_it = max(3, min(args.steps, 10))
+        tot = {s: 0.0 for s in stages}
+        for s_name in stages:
+            for _ in range(n_it):
+                L.forward(x)                      # inputs of the stage are those of a real step
+                flush.fill_(1.0)                  # 512 MiB written: nothing of the step stays cached
+                pair = (mk(), mk())
+                L.forward(x, trace={s_name: pair}, only=s_name)
+                torch.cuda.synchronize()
+                tot[s_name] += pair[0].elapsed_time(pair[1])
+        isolated = {s_name: {"ms": tot[s_name] / n_it} for s_name in stages}
+
+    input_hashes = None
+    if args.hash_inputs:
+        import hashlib
+        arrs = {"x": x_h, "W_g": Wg_h, "bias": bias_h, "w_gate": wg_h, "w_up": wu_h, "w_down": wd_h,
+                "x_profile": x_prof_h}
+        if shared_h is not None:
+            arrs.update({"shared_w_gate": shared_h[0], "shared_w_up": shared_h[1], "shared_w_down": shared_h[2]})
+        input_hashes = {k: {"shape": list(np.shape(v)), "sha256": hashlib.sha256(np.ascontiguousarray(v).tobytes()).hexdigest()}
+                        for k, v in arrs.items() if v is not None}
+
     # ---- CPU oracle on a bounded sample of the same workload (rank 0, N = 1) ----
     cpu = None
     if args.cpu_sample > 0:
@@ -220,11 +279,16 @@ def main():
                                f"{' + Zipf(1.1) offsets' if w.zipf else ''}, profiled on {w.T_profile or w.T} tokens",
                    "rows_routed_local": n_local, "router": "fp32, canonical chunk order"},
         "roofline": roofline, "cpu_baseline": cpu, "stages": stage_info,
+        "measured_ceilings": ceilings,
         "schedule": ("two streams: shared gate/up beside route+permute, routed gate/up alone, the two down passes "
                      "side by side; stage times are spans on their own stream and overlap") if L.overlap
                     else "one stream, stages back to back",
         "setup_s": t_gen,
     }
+    if isolated is not None:
+        out["stages_isolated_after_cache_flush"] = isolated
+    if input_hashes is not None:
+        out["inputs"] = {"seed_base": wl.SEED_BASE if hasattr(wl, "SEED_BASE") else None, "arrays": input_hashes}
     print(json.dumps(out))
 
 

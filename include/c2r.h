@@ -208,6 +208,21 @@ int c2r_expert_ffn_gate_up_gather(const void *x, c2r_dtype dt, const int32_t *pe
 int c2r_combine(const void *y_perm, c2r_dtype dt, const float *gates, const int32_t *inv_perm,
                 int64_t T, int d, int K, const void *y_shared, void *y, void *stream);
 
+/*
+ * Measurement aid, not a step of the path (Sec. 4 reports efficiency; no passage defines
+ * this operation): a loop of independent bf16 matrix instructions
+ * (v_mfma_f32_16x16x32_bf16) on register operands, used by the benchmark to report the
+ * matrix pipe's measured ceiling on this chip next to the vendor peak.
+ * operands : 1024 x 16 bytes of bf16 in DEVICE memory (values set the power drawn:
+ *            zeros reach the clock-limited peak, random values are power limited)
+ * iters    : loop trips; every wave issues 8 matrix instructions per trip
+ * blocks   : workgroups of 512 threads (1..65536)
+ * out      : float[blocks * 512] in DEVICE memory (sums, so the loop is not removed)
+ * flops    : HOST pointer or NULL; receives the floating-point operations of the launch
+ */
+int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -23,7 +23,8 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
 
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
-           "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine"]
+           "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine",
+           "c2r_probe_mfma_bf16"]
 
 
 class C2RError(RuntimeError):
@@ -58,6 +59,7 @@ def lib():
         L.c2r_expert_ffn_gate_up_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
         L.c2r_expert_ffn_down.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp]
         L.c2r_combine.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp]
+        L.c2r_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i32
         _lib = L
@@ -239,6 +241,15 @@ def combine(y_perm, gates, inv_perm, y_shared=None, out=None):
     return y
 
 
+def probe_mfma_bf16(operands, iters, blocks, out):
+    """Measurement aid: a pure bf16 matrix-instruction loop.  Returns the launch's flops."""
+    assert operands.numel() * operands.element_size() >= 1024 * 16 and out.numel() >= blocks * 512
+    fl = C.c_double(0.0)
+    _check("c2r_probe_mfma_bf16", lib().c2r_probe_mfma_bf16(_ptr(operands), iters, blocks, _ptr(out), C.byref(fl),
+                                                          _stream()))
+    return fl.value
+
+
 class C2RLayer:
     """One C2R MoE layer with all buffers allocated up front: forward() only
     enqueues the library's stages (no allocation, no host synchronisation).
@@ -300,14 +311,17 @@ class C2RLayer:
     # names of the stages forward() runs, in the order a trace lists them
     STAGES = ("route", "permute", "ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down", "combine")
 
-    def forward(self, x, trace=None):
+    def forward(self, x, trace=None, only=None):
         """y = layer(x).  trace: optional {stage: (start_event, end_event)} for any subset of
         STAGES; each pair is recorded on the stream its stage runs on (timing events, made by
-        the caller)."""
+        the caller).  only: run just that stage on the buffers a previous full call left
+        (for timing a stage on its own)."""
         main = torch.cuda.current_stream()
         side = self.side if self.overlap else main
 
         def run(name, stream, fn):
+            if only is not None and name != only:
+                return
             pair = trace.get(name) if trace is not None else None
             with torch.cuda.stream(stream):
                 if pair is not None:

@@ -1,0 +1,45 @@
+// Measured ceiling of the matrix pipe on this chip: a loop of independent
+// v_mfma_f32_16x16x32_bf16 on register operands, nothing else.  The benchmark reports it
+// next to the vendor peak (on random operands the chip is power limited well below it).
+#include "c2r_internal.h"
+
+namespace c2r {
+
+typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int PROBE_THREADS = 512, PROBE_ACC = 8;
+
+__global__ __launch_bounds__(PROBE_THREADS) void probe_mfma_kernel(const probe_bf16x8 *__restrict__ operands,
+                                                                  int iters, float *__restrict__ out) {
+    const probe_bf16x8 a = operands[threadIdx.x], b = operands[threadIdx.x + PROBE_THREADS];
+    probe_f32x4 acc[PROBE_ACC];
+#pragma unroll
+    for (int i = 0; i < PROBE_ACC; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) acc[i][v] = 0.0f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < PROBE_ACC; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < PROBE_ACC; ++i)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) s += acc[i][v];
+    out[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
+}
+
+}  // namespace c2r
+
+using namespace c2r;
+
+extern "C" int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops,
+                                   void *stream) {
+    if (!operands || !out || iters < 1 || blocks < 1 || blocks > 65536) return C2R_ERR_INVALID_ARG;
+    if (!aligned(operands, 16)) return C2R_ERR_INVALID_ARG;
+    probe_mfma_kernel<<<dim3((unsigned)blocks), dim3(PROBE_THREADS), 0, static_cast<hipStream_t>(stream)>>>(
+        static_cast<const probe_bf16x8 *>(operands), iters, out);
+    if (flops) *flops = (double)blocks * (PROBE_THREADS / 64) * (double)iters * PROBE_ACC * (2.0 * 16 * 16 * 32);
+    return launch_status();
+}

@@ -20,7 +20,7 @@ def test_header_symbols_exported():
     c2r = _lib()
     with open(os.path.join(ROOT, "include", "c2r.h")) as f:
         text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
-    declared = sorted(set(re.findall(r"\b(c2r_[a-z_]+)\s*\(", text)))
+    declared = sorted(set(re.findall(r"\b(c2r_[a-z0-9_]+)\s*\(", text)))
     assert declared == sorted(c2r.EXPORTS)
     L = c2r.lib()
     for name in declared:

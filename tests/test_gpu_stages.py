@@ -268,3 +268,14 @@ def test_combine(c2r, orc, dtype, T, K, d):
         ref = orc.combine(yp, g32, inv, T, K, shared)
         tol = 2.0 ** -8 if dtype == "bf16" else 1e-6                    # one rounding of the result
         assert np.abs(host(y) - ref).max() <= tol * max(np.abs(ref).max(), 1.0)
+
+
+def test_probe_mfma_counts_its_work(c2r):
+    # operands all ones: every 16x16x32 matrix instruction adds 32 to each of the lane's 4
+    # accumulator values; 8 accumulators, 3 trips -> each thread's sum is 3 * 8 * 4 * 32
+    ops = torch.ones(1024 * 8, dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(4 * 512, dtype=torch.float32, device="cuda")
+    flops = c2r.probe_mfma_bf16(ops, 3, 4, out)
+    torch.cuda.synchronize()
+    assert flops == 4 * 8 * 3 * 8 * 2 * 16 * 16 * 32
+    assert torch.all(out == 3 * 8 * 4 * 32)
