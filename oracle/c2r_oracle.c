@@ -311,3 +311,62 @@ void orc_distinct_devices(const int32_t *topk_idx, int64_t T, int K, const int32
         distinct[t] = n;
     }
 }
+
+/* ---- Sec. 3.4: zero-redundancy dispatch.  A token goes ONCE to every device that hosts at
+ * least one of its selected experts and is replicated there.  The send list is ordered by
+ * device, then by token; send_row[t*K+s] is the position in that list of the copy that slot
+ * s of token t uses (-1: empty slot or expert without a device).  send_offsets has n_dev+1
+ * entries.  Returns the number of copies sent. ---- */
+int64_t orc_dedup_dispatch(const int32_t *topk_idx, int64_t T, int K, int E, const int32_t *dev_of_expert,
+                           int n_dev, int32_t *send_counts, int32_t *send_offsets, int32_t *send_token,
+                           int32_t *send_row) {
+    int64_t n = 0;
+    for (int64_t a = 0; a < T * K; ++a) send_row[a] = -1;
+    for (int g = 0; g < n_dev; ++g) {
+        send_offsets[g] = (int32_t)n;
+        for (int64_t t = 0; t < T; ++t) {
+            int hit = 0;
+            for (int s = 0; s < K; ++s) {
+                int32_t e = topk_idx[t * K + s];
+                if (e >= 0 && e < E && dev_of_expert[e] == g) {
+                    hit = 1;
+                    send_row[t * K + s] = (int32_t)n;
+                }
+            }
+            if (hit) send_token[n++] = (int32_t)t;
+        }
+        send_counts[g] = (int32_t)n - send_offsets[g];
+    }
+    send_offsets[n_dev] = (int32_t)n;
+    return n;
+}
+
+/* The combine that goes with it: every device first adds up, gate-weighted, the outputs of
+ * its own experts for each token copy it received (one partial row per copy, y_part), and
+ * the token's home device adds the partial rows of its copies (+ the shared expert). */
+void orc_combine_partial(const double *y_perm, const double *gates, const int32_t *inv_perm,
+                         const int32_t *send_row, int64_t T, int d, int K, int64_t n_send, double *y_part) {
+    memset(y_part, 0, sizeof(double) * (size_t)n_send * d);
+    for (int64_t t = 0; t < T; ++t)
+        for (int s = 0; s < K; ++s) {
+            int32_t r = send_row[t * K + s], p = inv_perm[t * K + s];
+            if (r < 0 || p < 0) continue;
+            for (int j = 0; j < d; ++j) y_part[(int64_t)r * d + j] += gates[t * K + s] * y_perm[(int64_t)p * d + j];
+        }
+}
+
+void orc_combine_copies(const double *y_part, const int32_t *send_row, int64_t T, int d, int K,
+                        const double *y_shared, double *y) {
+    for (int64_t t = 0; t < T; ++t)
+        for (int j = 0; j < d; ++j) {
+            double acc = 0.0;
+            for (int s = 0; s < K; ++s) {
+                int32_t r = send_row[t * K + s];
+                int seen = r < 0;
+                for (int b = 0; b < s && !seen; ++b) seen = send_row[t * K + b] == r;
+                if (!seen) acc += y_part[(int64_t)r * d + j];
+            }
+            if (y_shared) acc += y_shared[t * d + j];
+            y[t * d + j] = acc;
+        }
+}

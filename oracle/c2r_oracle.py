@@ -188,3 +188,38 @@ def redundancy(distinct, K):
 def estimated_speedup(all_to_all_share, redundancy_share):
     """Sec. 4.1: estimated speed-up = all-to-all time share x token redundancy."""
     return all_to_all_share * redundancy_share
+
+
+# ---- Sec. 3.4: zero-redundancy dispatch (one copy of a token per destination device) ----
+
+def dedup_dispatch(topk_idx, E, dev_of_expert, n_dev):
+    """Returns (send_counts[n_dev], send_offsets[n_dev+1], send_token[n_send], send_row[T*K])."""
+    idx = _i32(topk_idx)
+    T, K = idx.shape
+    dev = _i32(dev_of_expert)
+    counts = np.empty(n_dev, dtype=np.int32)
+    offsets = np.empty(n_dev + 1, dtype=np.int32)
+    tok = np.empty(T * K, dtype=np.int32)
+    row = np.empty(T * K, dtype=np.int32)
+    lib().orc_dedup_dispatch.restype = C.c_int64
+    n = lib().orc_dedup_dispatch(_p(idx), C.c_int64(T), K, E, _p(dev), n_dev, _p(counts), _p(offsets), _p(tok), _p(row))
+    return counts, offsets, tok[:n].copy(), row
+
+
+def combine_partial(y_perm, gates, inv_perm, send_row, T, K, n_send):
+    yp = np.ascontiguousarray(y_perm, dtype=np.float64)
+    d = yp.shape[1]
+    g = np.ascontiguousarray(gates, dtype=np.float64)
+    out = np.empty((n_send, d), dtype=np.float64)
+    lib().orc_combine_partial(_p(yp), _p(g), _p(_i32(inv_perm)), _p(_i32(send_row)), C.c_int64(T), d, K,
+                              C.c_int64(n_send), _p(out))
+    return out
+
+
+def combine_copies(y_part, send_row, T, K, y_shared=None):
+    yp = np.ascontiguousarray(y_part, dtype=np.float64)
+    d = yp.shape[1]
+    ys = None if y_shared is None else np.ascontiguousarray(y_shared, dtype=np.float64)
+    y = np.empty((T, d), dtype=np.float64)
+    lib().orc_combine_copies(_p(yp), _p(_i32(send_row)), C.c_int64(T), d, K, _p(ys), _p(y))
+    return y

@@ -345,6 +345,66 @@ def test_distinct_devices_and_redundancy(orc):
     assert orc.redundancy(np.full(10, 4), 4) == 0.0
 
 
+def test_dedup_dispatch_properties(orc):
+    # Sec. 3.4: one copy of a token per device that hosts one of its experts.  Pinned by the
+    # definition written out with Python sets, by the copy count = sum of distinct devices
+    # (pinned above), and by three closed forms.
+    E, K, n_dev = 12, 4, 4
+    idx, _ = orc.route(_small_logits(300, E, 23), K)
+    idx[5, 2] = -1                                           # an empty slot sends nothing
+    dev = wl.device_map(E, n_dev)
+    counts, offsets, tok, row = orc.dedup_dispatch(idx, E, dev, n_dev)
+    pairs = sorted({(int(dev[e]), t) for t in range(idx.shape[0]) for e in idx[t] if e >= 0})
+    assert [(g, t) for g in range(n_dev) for t in tok[offsets[g]:offsets[g + 1]]] == pairs
+    assert list(counts) == [sum(1 for g, _ in pairs if g == q) for q in range(n_dev)]
+    assert offsets[0] == 0 and offsets[-1] == len(pairs) and np.all(np.diff(offsets) == counts)
+    row = row.reshape(idx.shape)
+    for t in range(idx.shape[0]):
+        for s in range(K):
+            e = idx[t, s]
+            if e < 0:
+                assert row[t, s] == -1
+            else:                                            # the copy slot s uses is (device of e, t)
+                assert tok[row[t, s]] == t and offsets[dev[e]] <= row[t, s] < offsets[dev[e] + 1]
+    idx[5, 2] = 0
+    _, offsets, tok, _ = orc.dedup_dispatch(idx, E, dev, n_dev)
+    assert len(tok) == orc.distinct_devices(idx, dev).sum()
+    # closed forms: one device -> every token once; one expert per device -> nothing saved;
+    # K = 1 -> the send list is the tokens sorted by their expert's device
+    _, _, tok1, row1 = orc.dedup_dispatch(idx, E, np.zeros(E, dtype=np.int32), 1)
+    assert list(tok1) == list(range(idx.shape[0])) and np.all(row1.reshape(idx.shape) == np.arange(idx.shape[0])[:, None])
+    _, _, tokE, _ = orc.dedup_dispatch(idx, E, np.arange(E, dtype=np.int32), E)
+    assert len(tokE) == idx.size
+    one = idx[:, :1].copy()
+    _, _, tokK, _ = orc.dedup_dispatch(one, E, dev, n_dev)
+    assert list(tokK) == sorted(range(one.shape[0]), key=lambda t: (dev[one[t, 0]], t))
+
+
+def test_two_level_combine_equals_combine(orc):
+    # adding a token's expert outputs per device first and the per-device partial rows second
+    # is the same sum: exact on integer-valued inputs, whatever the grouping
+    rng = np.random.default_rng(24)
+    T, E, K, d, n_dev = 200, 10, 3, 6, 5
+    idx, _ = orc.route(_small_logits(T, E, 25), K)
+    g = rng.integers(1, 5, size=(T, K)).astype(np.float64)
+    ls = np.arange(E, dtype=np.int32)
+    ls[3] = -1
+    ls[4:] -= 1                                              # expert 3 is not computed here
+    _, _, perm, inv = orc.permute(idx, E, ls, E - 1)
+    yp = rng.integers(-8, 9, size=(len(perm), d)).astype(np.float64)
+    ys = rng.integers(-8, 9, size=(T, d)).astype(np.float64)
+    dev = wl.device_map(E, n_dev)
+    _, _, tok, row = orc.dedup_dispatch(idx, E, dev, n_dev)
+    part = orc.combine_partial(yp, g, inv, row, T, K, len(tok))
+    for shared in (None, ys):
+        assert np.array_equal(orc.combine_copies(part, row, T, K, shared), orc.combine(yp, g, inv, T, K, shared))
+    # a copy's partial row holds exactly the terms of the experts on its device
+    r = row.reshape(T, K)
+    t, s = 17, 1
+    same = [q for q in range(K) if r[t, q] == r[t, s] and inv[t * K + q] >= 0]
+    assert np.array_equal(part[r[t, s]], sum(g[t, q] * yp[inv[t * K + q]] for q in same))
+
+
 def test_table3_speedup_product(orc):
     # P10: the printed speed-ups are the products of the printed shares (inputs are rounded,
     # so agree to 0.1 point)
