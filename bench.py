@@ -138,6 +138,43 @@ def main():
     torch.cuda.synchronize()
     permute_rows_ms = e0.elapsed_time(e1) / args.steps
 
+    # Sec. 3.4 on one GPU (outside the step): the zero-redundancy send list for a fixed contiguous
+    # 4-device map and the two-level combine that goes with it
+    n_dev = 4
+    dm = dev(wl.device_map(w.E, n_dev))
+    zr = {}
+    ws_dd = torch.empty(max(256, c2r.workspace_bytes(c2r.STAGE_DEDUP_DISPATCH, w.T, 0, n_dev, w.K, 0, c2r.F32)),
+                        dtype=torch.uint8, device="cuda")
+    y_part = torch.empty((w.T * w.K, w.d), dtype=tdt, device="cuda")
+    y_zr = torch.empty((w.T, w.d), dtype=tdt, device="cuda")
+    for _ in range(args.warmup):
+        _, zoff, ztok, zrow = c2r.dedup_dispatch(L.idx, w.E, dm, n_dev, ws=ws_dd)
+        c2r.combine_partial(L.y_perm, L.gates, L.inv_perm, ztok, zrow, zoff, y_part=y_part)
+        c2r.combine_copies(y_part, zrow, w.T, w.K, L.y_shared, out=y_zr)
+    ez = [mk() for _ in range(4)]
+    ez[0].record()
+    for _ in range(args.steps):
+        _, zoff, ztok, zrow = c2r.dedup_dispatch(L.idx, w.E, dm, n_dev, ws=ws_dd)
+    ez[1].record()
+    for it in range(args.steps):
+        c2r.combine_partial(L.y_perm, L.gates, L.inv_perm, ztok, zrow, zoff, y_part=y_part)
+    ez[2].record()
+    for it in range(args.steps):
+        c2r.combine_copies(y_part, zrow, w.T, w.K, L.y_shared, out=y_zr)
+    ez[3].record()
+    torch.cuda.synchronize()
+    n_send = int(zoff[-1].item())
+    zr_ms = [ez[i].elapsed_time(ez[i + 1]) / args.steps for i in range(3)]
+    part_bytes = (int(L.offsets[-1].item()) + n_send) * w.d * sz
+    copies_bytes = (n_send + (2 if shared else 1) * w.T) * w.d * sz
+    zr = {"devices": n_dev, "copies_sent": n_send, "copies_per_token": n_send / w.T,
+          "redundancy": 1.0 - n_send / (w.T * w.K),
+          "dedup_dispatch_ms": zr_ms[0],
+          "combine_partial": {"ms": zr_ms[1], "GBps": part_bytes / zr_ms[1] / 1e6,
+                              "frac_hbm": part_bytes / zr_ms[1] / 1e6 / PEAK["hbm_GBps"]},
+          "combine_copies": {"ms": zr_ms[2], "GBps": copies_bytes / zr_ms[2] / 1e6,
+                             "frac_hbm": copies_bytes / zr_ms[2] / 1e6 / PEAK["hbm_GBps"]}}
+
     # ---- algorithmic work per stage ----
     n_local = int(L.offsets[-1].item())          # rows the local experts process
     A = w.T * w.K
@@ -279,7 +316,7 @@ def main():
                                f"{' + Zipf(1.1) offsets' if w.zipf else ''}, profiled on {w.T_profile or w.T} tokens",
                    "rows_routed_local": n_local, "router": "fp32, canonical chunk order"},
         "roofline": roofline, "cpu_baseline": cpu, "stages": stage_info,
-        "measured_ceilings": ceilings,
+        "measured_ceilings": ceilings, "zero_redundancy_dispatch": zr,
         "schedule": ("two streams: shared gate/up beside route+permute, routed gate/up alone, the two down passes "
                      "side by side; stage times are spans on their own stream and overlap") if L.overlap
                     else "one stream, stages back to back",

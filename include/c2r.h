@@ -49,7 +49,8 @@ typedef enum {
     C2R_STAGE_COACTIVATION = 0,
     C2R_STAGE_ROUTE = 1,
     C2R_STAGE_PERMUTE = 2,
-    C2R_STAGE_EXPERT_FFN = 3
+    C2R_STAGE_EXPERT_FFN = 3,
+    C2R_STAGE_DEDUP_DISPATCH = 4 /* pass the number of devices as E */
 } c2r_stage;
 
 /* Library version (major*10000 + minor*100 + patch). */
@@ -207,6 +208,49 @@ int c2r_expert_ffn_gate_up_gather(const void *x, c2r_dtype dt, const int32_t *pe
  */
 int c2r_combine(const void *y_perm, c2r_dtype dt, const float *gates, const int32_t *inv_perm,
                 int64_t T, int d, int K, const void *y_shared, void *y, void *stream);
+
+/*
+ * Zero-redundancy dispatch index (Sec. 3.4: "sends only a single copy of the token to the
+ * shared device, where it is subsequently replicated locally"), built on one GPU.  For a
+ * map expert -> device, every token gets ONE copy per device that hosts at least one of its
+ * selected experts.  The copies are listed device after device, tokens ascending:
+ *   send_counts[g], send_offsets[g]   : copies for device g (send_offsets has n_dev+1 entries,
+ *                                       the last one the total n_send = sum over tokens of
+ *                                       the number of distinct devices of their experts)
+ *   send_token[send_offsets[g] + i]   : the i-th token device g receives
+ *   send_row[t*K + s]                 : the position in send_token of the copy that slot s of
+ *                                       token t uses on its expert's device; -1 if the slot
+ *                                       is empty (topk_idx < 0 or >= E) or its expert has no
+ *                                       device (expert_device outside [0, n_dev))
+ * 1 - n_send / (T*K) is the token redundancy of Sec. 4.1.
+ * topk_idx : int32[T,K]; expert_device : int32[E]; n_dev <= 64
+ * send_counts int32[n_dev], send_offsets int32[n_dev+1], send_token int32[T*K] (capacity;
+ * entries past n_send untouched), send_row int32[T*K]: all DEVICE memory, all out.
+ * ws : c2r_workspace_bytes(C2R_STAGE_DEDUP_DISPATCH, T, 0, n_dev, K, 0, C2R_F32)
+ * Deterministic (no atomically assigned positions), integer results exact.
+ */
+int c2r_dedup_dispatch(const int32_t *topk_idx, int64_t T, int K, int E, const int32_t *expert_device,
+                       int n_dev, int32_t *send_counts, int32_t *send_offsets, int32_t *send_token,
+                       int32_t *send_row, void *ws, size_t ws_bytes, void *stream);
+
+/*
+ * The combine that goes with it (Sec. 3.4, Sec. 3.1 last sentence), in two levels.
+ * c2r_combine_partial is what an expert device returns: one row per token copy r,
+ *     y_part[r] = sum_{s : send_row[t*K+s] == r, inv_perm[t*K+s] >= 0} gates[t,s] * y_perm[inv_perm[t*K+s]]
+ * with t = send_token[r], summed in fp32 in slot order and rounded once to dt.
+ * c2r_combine_copies is what the token's home device does:
+ *     y[t] = sum over the distinct rows r among send_row[t*K + 0..K-1], in order of first
+ *            appearance, of y_part[r]  (+ y_shared[t]),  fp32, rounded once to dt.
+ * Against c2r_combine the result differs only by the extra rounding of the partial rows.
+ * n_send   : DEVICE pointer to the number of copies (&send_offsets[n_dev])
+ * cap_rows : rows allocated in y_part (>= *n_send, e.g. T*K); rows >= *n_send untouched
+ * y_part   : [cap_rows, d] of dt;  y_shared : [T, d] of dt or NULL;  y : [T, d] of dt out
+ */
+int c2r_combine_partial(const void *y_perm, c2r_dtype dt, const float *gates, const int32_t *inv_perm,
+                        const int32_t *send_token, const int32_t *send_row, const int32_t *n_send,
+                        int64_t T, int64_t cap_rows, int d, int K, void *y_part, void *stream);
+int c2r_combine_copies(const void *y_part, c2r_dtype dt, const int32_t *send_row, int64_t T,
+                       int64_t cap_rows, int d, int K, const void *y_shared, void *y, void *stream);
 
 /*
  * Measurement aid, not a step of the path (Sec. 4 reports efficiency; no passage defines

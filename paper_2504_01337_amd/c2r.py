@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libc2r_hip.so")
 
 F32, BF16 = 0, 1
-STAGE_COACTIVATION, STAGE_ROUTE, STAGE_PERMUTE, STAGE_EXPERT_FFN = 0, 1, 2, 3
+STAGE_COACTIVATION, STAGE_ROUTE, STAGE_PERMUTE, STAGE_EXPERT_FFN, STAGE_DEDUP_DISPATCH = 0, 1, 2, 3, 4
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_LAUNCH = 0, -1, -2, -3, -4
 _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_WORKSPACE",
              -4: "C2R_ERR_LAUNCH"}
@@ -24,7 +24,7 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine",
-           "c2r_probe_mfma_bf16"]
+           "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies", "c2r_probe_mfma_bf16"]
 
 
 class C2RError(RuntimeError):
@@ -59,6 +59,9 @@ def lib():
         L.c2r_expert_ffn_gate_up_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
         L.c2r_expert_ffn_down.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp]
         L.c2r_combine.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp]
+        L.c2r_dedup_dispatch.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
+        L.c2r_combine_partial.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
+        L.c2r_combine_copies.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp]
         L.c2r_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i32
@@ -238,6 +241,43 @@ def combine(y_perm, gates, inv_perm, y_shared=None, out=None):
     y = torch.empty((T, d), dtype=y_perm.dtype, device=y_perm.device) if out is None else out
     _check("c2r_combine", lib().c2r_combine(_ptr(y_perm), _dt(y_perm), _ptr(gates), _ptr(inv_perm), T, d, K,
                                             _ptr(y_shared), _ptr(y), _stream()))
+    return y
+
+
+def dedup_dispatch(topk_idx, E, expert_device, n_dev, ws=None):
+    """Sec. 3.4: one copy of a token per destination device.
+    Returns (send_counts[n_dev], send_offsets[n_dev+1], send_token[T*K], send_row[T*K])."""
+    T, K = topk_idx.shape
+    dev = topk_idx.device
+    i32 = dict(dtype=torch.int32, device=dev)
+    counts, offsets = torch.empty((n_dev,), **i32), torch.empty((n_dev + 1,), **i32)
+    tok, row = torch.full((T * K,), -1, **i32), torch.empty((T * K,), **i32)
+    ws = _ws(workspace_bytes(STAGE_DEDUP_DISPATCH, T, 0, n_dev, K, 0, F32), dev, ws)
+    _check("c2r_dedup_dispatch", lib().c2r_dedup_dispatch(_ptr(topk_idx), T, K, E, _ptr(expert_device), n_dev,
+                                                        _ptr(counts), _ptr(offsets), _ptr(tok), _ptr(row),
+                                                        _ptr(ws), ws.numel(), _stream()))
+    return counts, offsets, tok, row
+
+
+def combine_partial(y_perm, gates, inv_perm, send_token, send_row, send_offsets, y_part=None):
+    """What an expert device returns: one gate-weighted partial row per token copy."""
+    T, K = gates.shape
+    d = y_perm.shape[1]
+    if y_part is None:
+        y_part = torch.empty((T * K, d), dtype=y_perm.dtype, device=y_perm.device)
+    n_send = send_offsets[-1:]
+    _check("c2r_combine_partial", lib().c2r_combine_partial(_ptr(y_perm), _dt(y_perm), _ptr(gates), _ptr(inv_perm),
+                                                          _ptr(send_token), _ptr(send_row), _ptr(n_send), T,
+                                                          y_part.shape[0], d, K, _ptr(y_part), _stream()))
+    return y_part
+
+
+def combine_copies(y_part, send_row, T, K, y_shared=None, out=None):
+    """What the token's home device does: add the partial rows of its copies (+ shared)."""
+    d = y_part.shape[1]
+    y = torch.empty((T, d), dtype=y_part.dtype, device=y_part.device) if out is None else out
+    _check("c2r_combine_copies", lib().c2r_combine_copies(_ptr(y_part), _dt(y_part), _ptr(send_row), T,
+                                                        y_part.shape[0], d, K, _ptr(y_shared), _ptr(y), _stream()))
     return y
 
 

@@ -5,6 +5,7 @@
 namespace c2r {
 size_t route_workspace_bytes(int64_t T, int d, int E);
 size_t permute_workspace_bytes(int64_t T, int E, int K);
+size_t dedup_workspace_bytes(int64_t T, int n_dev);
 int launch_ffn_f32_pass(int pass, const float *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
                         int F, const float *b0, const float *b1, float *out, hipStream_t st);
 int launch_ffn_bf16_pass(int pass, const uint16_t *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
@@ -43,6 +44,8 @@ extern "C" size_t c2r_workspace_bytes(int stage, int64_t T, int d, int E, int K,
             const size_t sz = dt == C2R_BF16 ? 2 : 4;
             return round_up((size_t)T * (size_t)(K > 0 ? K : 1) * (size_t)h_pitch(dt, d, F) * sz, 256);
         }
+        case C2R_STAGE_DEDUP_DISPATCH:
+            return dedup_workspace_bytes(T, E);  // E: number of devices
         default:
             return 0;
     }

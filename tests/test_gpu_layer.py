@@ -87,12 +87,26 @@ def test_layer_reduced(c2r, orc, name, T, Tp):
 def test_layer_full_size(c2r, orc, name):
     w = wl.WORKLOADS[name]
     layer, o = _run_layer(c2r, orc, w, n_sample=48)
-    if name == "C5":
-        # Sec. 3.4: distinct devices per token under a fixed 4-way contiguous map, host side
+    if name in ("C3", "C5"):
+        # Sec. 3.4 at full size: the zero-redundancy send list under a fixed 4-way contiguous map
+        # (bit exact), its copy count against the host-side count of distinct devices, and the
+        # two-level combine against the layer's own output
         dm = wl.device_map(w.E, 4)
+        counts, offsets, tok, row = c2r.dedup_dispatch(layer.idx, w.E, dev(dm), 4)
+        rc, ro, rt, rr = orc.dedup_dispatch(o.idx, w.E, dm, 4)
+        n = int(ro[-1])
+        assert np.array_equal(host(offsets), ro) and np.array_equal(host(tok)[:n], rt) and np.array_equal(host(row), rr)
+        dd = orc.distinct_devices(o.idx, dm)
+        assert n == int(dd.sum())
         idx_topk, _ = orc.route(o.logits, w.K)
-        print("[layer] C5 mean distinct devices/token: C2R %.3f, top-K %.3f" % (
-            orc.distinct_devices(o.idx, dm).mean(), orc.distinct_devices(idx_topk, dm).mean()), flush=True)
+        print("[layer] %s copies sent per token (4 devices): C2R %.3f, top-K %.3f; redundancy %.3f vs %.3f" % (
+            name, dd.mean(), orc.distinct_devices(idx_topk, dm).mean(), orc.redundancy(dd, w.K),
+            orc.redundancy(orc.distinct_devices(idx_topk, dm), w.K)), flush=True)
+        part = c2r.combine_partial(layer.y_perm, layer.gates, layer.inv_perm, tok, row, offsets)
+        y2 = c2r.combine_copies(part, row, w.T, w.K, layer.y_shared)
+        torch.cuda.synchronize()
+        ref = host(layer.y)
+        assert np.abs(host(y2) - ref).max() <= 2.0 ** -7 * np.abs(ref).max()   # one more rounding than c2r_combine
 
 
 def test_profiling_c4_full_size(c2r, orc):

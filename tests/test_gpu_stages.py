@@ -279,3 +279,54 @@ def test_probe_mfma_counts_its_work(c2r):
     torch.cuda.synchronize()
     assert flops == 4 * 8 * 3 * 8 * 2 * 16 * 16 * 32
     assert torch.all(out == 3 * 8 * 4 * 32)
+
+
+@pytest.mark.parametrize("E,K,T,n_dev,holes", [(12, 4, 300, 4, True), (60, 4, 5000, 4, False), (64, 8, 1025, 64, True),
+                                               (8, 2, 1, 2, False), (60, 4, 8192, 6, False), (16, 1, 4100, 3, True)])
+def test_dedup_dispatch(c2r, orc, E, K, T, n_dev, holes):
+    """Sec. 3.4: send list (device-major, tokens ascending) and copy row per assignment, bit exact."""
+    rng = np.random.default_rng(E * 13 + T)
+    idx, _ = orc.route(rng.standard_normal((T, E)).astype(np.float32), K)
+    devmap = (np.arange(E) * n_dev // E).astype(np.int32)
+    if holes:
+        idx = idx.copy()
+        idx[rng.integers(0, T, size=max(1, T // 7)), rng.integers(0, K, size=max(1, T // 7))] = -1   # empty slots
+        devmap[rng.integers(0, E)] = -1                                                               # expert without a device
+    counts, offsets, tok, row = c2r.dedup_dispatch(dev(idx), E, dev(devmap), n_dev)
+    rc, ro, rt, rr = orc.dedup_dispatch(idx, E, devmap, n_dev)
+    assert np.array_equal(host(counts), rc) and np.array_equal(host(offsets), ro)
+    n = int(ro[-1])
+    assert np.array_equal(host(tok)[:n], rt) and np.all(host(tok)[n:] == -1)
+    assert np.array_equal(host(row), rr)
+    if not holes:
+        assert n == int(orc.distinct_devices(idx, devmap).sum())
+
+
+@pytest.mark.parametrize("dtype,T,K,d,n_dev", [("f32", 300, 3, 64, 3), ("bf16", 2000, 4, 512, 4), ("bf16", 5, 2, 8, 2)])
+def test_two_level_combine(c2r, orc, dtype, T, K, d, n_dev):
+    rng = np.random.default_rng(T + d)
+    store = wl.round_bf16 if dtype == "bf16" else (lambda a: a)
+    E = 12
+    idx, g = orc.route(rng.standard_normal((T, E)).astype(np.float32), K)
+    ls = np.arange(E, dtype=np.int32)
+    ls[7] = -1
+    ls[8:] -= 1                                                          # expert 7 is not computed here
+    _, _, perm, inv = orc.permute(idx, E, ls, E - 1)
+    devmap = (np.arange(E) * n_dev // E).astype(np.int32)
+    yp = store(rng.standard_normal((T * K, d)).astype(np.float32))
+    ys = store(rng.standard_normal((T, d)).astype(np.float32))
+    g32 = g.astype(np.float32)
+    _, offsets, tok, row = c2r.dedup_dispatch(dev(idx), E, dev(devmap), n_dev)
+    _, ro, rt, rr = orc.dedup_dispatch(idx, E, devmap, n_dev)
+    part = c2r.combine_partial(dev(yp, dtype), dev(g32), dev(inv), tok, row, offsets)
+    n = int(ro[-1])
+    ref_part = orc.combine_partial(yp, g32, inv, rr, T, K, n)
+    tol = 2.0 ** -8 if dtype == "bf16" else 1e-6                         # one rounding per level
+    assert np.abs(host(part)[:n] - ref_part).max() <= tol * max(np.abs(ref_part).max(), 1.0)
+    for shared in (None, ys):
+        y = c2r.combine_copies(part, row, T, K, None if shared is None else dev(shared, dtype))
+        ref = orc.combine(yp, g32, inv, T, K, shared)                    # the same sum, grouped differently
+        assert np.abs(host(y) - ref).max() <= 2 * tol * max(np.abs(ref).max(), 1.0)
+        # and exactly the second level applied to the first level's (rounded) rows
+        ref2 = orc.combine_copies(host(part)[:n], rr, T, K, shared)
+        assert np.abs(host(y) - ref2).max() <= tol * max(np.abs(ref2).max(), 1.0)
