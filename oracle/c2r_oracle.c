@@ -370,3 +370,37 @@ void orc_combine_copies(const double *y_part, const int32_t *send_row, int64_t T
             y[t * d + j] = acc;
         }
 }
+
+/* ---- Sec. 3.4: "co-locate closely collaborating experts on the same computational units".
+ * The paper names the goal and gives no procedure; the reading taken is a greedy fill.
+ * Devices 0..n_dev-1 are filled one after the other, each with cap = ceil(E / n_dev) experts
+ * (the last ones with what is left).  A device starts with the unplaced expert whose
+ * co-activation with all other experts (its row of C without the diagonal) is largest, and
+ * then repeatedly takes the unplaced expert with the largest total co-activation with the
+ * experts already on the device.  Ties go to the lower index. ---- */
+void orc_place_experts(const int64_t *C, int E, int n_dev, int32_t *expert_device) {
+    int cap = (E + n_dev - 1) / n_dev;
+    for (int e = 0; e < E; ++e) expert_device[e] = -1;
+    for (int g = 0; g < n_dev; ++g) {
+        int members = 0;
+        while (members < cap) {
+            int best = -1;
+            int64_t best_score = 0;
+            for (int e = 0; e < E; ++e) {
+                if (expert_device[e] >= 0) continue;
+                int64_t score = 0;
+                for (int j = 0; j < E; ++j) {
+                    if (j == e) continue;
+                    if (members == 0 || expert_device[j] == g) score += C[(int64_t)e * E + j];
+                }
+                if (best < 0 || score > best_score) {
+                    best = e;
+                    best_score = score;
+                }
+            }
+            if (best < 0) break; /* everything is placed */
+            expert_device[best] = g;
+            ++members;
+        }
+    }
+}

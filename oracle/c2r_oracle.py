@@ -223,3 +223,12 @@ def combine_copies(y_part, send_row, T, K, y_shared=None):
     y = np.empty((T, d), dtype=np.float64)
     lib().orc_combine_copies(_p(yp), _p(_i32(send_row)), C.c_int64(T), d, K, _p(ys), _p(y))
     return y
+
+
+def place_experts(Cm, n_dev):
+    """Greedy co-location of collaborating experts (Sec. 3.4).  Returns int32[E] expert -> device."""
+    Cm = np.ascontiguousarray(Cm, dtype=np.int64)
+    E = Cm.shape[0]
+    out = np.empty(E, dtype=np.int32)
+    lib().orc_place_experts(_p(Cm), E, n_dev, _p(out))
+    return out

@@ -405,6 +405,36 @@ def test_two_level_combine_equals_combine(orc):
     assert np.array_equal(part[r[t, s]], sum(g[t, q] * yp[inv[t * K + q]] for q in same))
 
 
+def test_place_experts_recovers_planted_groups(orc):
+    # Sec. 3.4 co-location (greedy reading).  Pins: a block-structured C gives back its blocks;
+    # every expert is placed once and devices are filled in order up to ceil(E/n_dev); on small
+    # clear-cut inputs the greedy partition keeps as much co-activation inside devices as the
+    # best balanced partition found by enumeration.
+    rng = np.random.default_rng(31)
+    for E, n_dev in ((12, 4), (60, 4), (15, 5)):
+        cap = E // n_dev
+        label = rng.permutation(np.repeat(np.arange(n_dev), cap))
+        Cm = (label[:, None] == label[None, :]).astype(np.int64) * 100 + rng.integers(0, 10, size=(E, E))
+        Cm = Cm + Cm.T
+        dev = orc.place_experts(Cm, n_dev)
+        assert sorted(np.bincount(dev, minlength=n_dev)) == [cap] * n_dev
+        for g in range(n_dev):                               # a device holds exactly one planted group
+            assert len(set(label[dev == g])) == 1
+    dev = orc.place_experts(np.ones((10, 10), dtype=np.int64), 4)   # all ties: index order, 3+3+3+1
+    assert list(dev) == [0, 0, 0, 1, 1, 1, 2, 2, 2, 3]
+    E = 8
+    label = np.array([0, 1, 0, 1, 1, 0, 0, 1])
+    Cm = (label[:, None] == label[None, :]).astype(np.int64) * 20 + rng.integers(0, 4, size=(E, E))
+    Cm = Cm + Cm.T
+    inside = lambda d: sum(Cm[i, j] for i in range(E) for j in range(E) if i != j and d[i] == d[j])
+    best = max(inside(np.isin(np.arange(E), c).astype(int)) for c in itertools.combinations(range(E), 4))
+    assert inside(orc.place_experts(Cm, 2)) == best
+    # the first expert of device 0 is the one that collaborates most overall (lower index on ties)
+    Cm = rng.integers(0, 50, size=(9, 9)); Cm = Cm + Cm.T
+    off = Cm.sum(1) - np.diag(Cm)
+    assert orc.place_experts(Cm, 3)[int(np.argmax(off))] == 0
+
+
 def test_table3_speedup_product(orc):
     # P10: the printed speed-ups are the products of the printed shares (inputs are rounded,
     # so agree to 0.1 point)
