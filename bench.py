@@ -85,7 +85,8 @@ def main():
 
     # offline profiling (Sec. 3.2 / Eq. 4) on the GPU: conventional top-K -> C -> lists
     idx_p, _, _ = c2r.route(dev(x_prof_h, w.dtype), Wg, bias, w.K, None)
-    collab, _ = c2r.collaborators(c2r.build_coactivation(idx_p, w.E), w.Tc)
+    Cm = c2r.build_coactivation(idx_p, w.E)
+    collab, _ = c2r.collaborators(Cm, w.Tc)
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
 
@@ -167,8 +168,18 @@ def main():
     zr_ms = [ez[i].elapsed_time(ez[i + 1]) / args.steps for i in range(3)]
     part_bytes = (int(L.offsets[-1].item()) + n_send) * w.d * sz
     copies_bytes = (n_send + (2 if shared else 1) * w.T) * w.d * sz
+    # the same count with experts co-located by their profiled co-activation (c2r_place_experts),
+    # for this routing and for plain top-K of the same router
+    placed = c2r.place_experts(Cm, n_dev)
+    n_placed = int(c2r.dedup_dispatch(L.idx, w.E, placed, n_dev)[1][-1].item())
+    idx_topk, _, _ = c2r.route(x, Wg, bias, w.K, None)
+    n_placed_topk = int(c2r.dedup_dispatch(idx_topk, w.E, placed, n_dev)[1][-1].item())
+    n_topk = int(c2r.dedup_dispatch(idx_topk, w.E, dm, n_dev)[1][-1].item())
+    red = lambda n: 1.0 - n / (w.T * w.K)
     zr = {"devices": n_dev, "copies_sent": n_send, "copies_per_token": n_send / w.T,
           "redundancy": 1.0 - n_send / (w.T * w.K),
+          "redundancy_by_map_and_routing": {"contiguous_map": {"c2r": red(n_send), "top_k": red(n_topk)},
+                                            "co_located_map": {"c2r": red(n_placed), "top_k": red(n_placed_topk)}},
           "dedup_dispatch_ms": zr_ms[0],
           "combine_partial": {"ms": zr_ms[1], "GBps": part_bytes / zr_ms[1] / 1e6,
                               "frac_hbm": part_bytes / zr_ms[1] / 1e6 / PEAK["hbm_GBps"]},

@@ -234,6 +234,18 @@ int c2r_dedup_dispatch(const int32_t *topk_idx, int64_t T, int K, int E, const i
                        int32_t *send_row, void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * Expert -> device map that co-locates collaborating experts (Sec. 3.4: "we can co-locate
+ * closely collaborating experts on the same computational units"; the paper names the goal
+ * and gives no procedure - this is a greedy fill).  Devices 0..n_dev-1 are filled in order
+ * with ceil(E / n_dev) experts each (the last ones with what is left): a device starts with
+ * the unplaced expert whose row of C, diagonal left out, sums highest, and then keeps taking
+ * the unplaced expert with the largest total co-activation with the experts already on it;
+ * ties go to the lower index.  Co-activation counts are non-negative (Eq. 2).
+ * C : int32[E,E] (DEVICE, as c2r_build_coactivation leaves it); expert_device : int32[E] out.
+ */
+int c2r_place_experts(const int32_t *C, int E, int n_dev, int32_t *expert_device, void *stream);
+
+/*
  * The combine that goes with it (Sec. 3.4, Sec. 3.1 last sentence), in two levels.
  * c2r_combine_partial is what an expert device returns: one row per token copy r,
  *     y_part[r] = sum_{s : send_row[t*K+s] == r, inv_perm[t*K+s] >= 0} gates[t,s] * y_perm[inv_perm[t*K+s]]

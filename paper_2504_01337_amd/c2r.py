@@ -24,7 +24,7 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine",
-           "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies", "c2r_probe_mfma_bf16"]
+           "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies", "c2r_probe_mfma_bf16"]
 
 
 class C2RError(RuntimeError):
@@ -59,6 +59,7 @@ def lib():
         L.c2r_expert_ffn_gate_up_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
         L.c2r_expert_ffn_down.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp]
         L.c2r_combine.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp]
+        L.c2r_place_experts.argtypes = [vp, i32, i32, vp, vp]
         L.c2r_dedup_dispatch.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_combine_partial.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
         L.c2r_combine_copies.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp]
@@ -242,6 +243,14 @@ def combine(y_perm, gates, inv_perm, y_shared=None, out=None):
     _check("c2r_combine", lib().c2r_combine(_ptr(y_perm), _dt(y_perm), _ptr(gates), _ptr(inv_perm), T, d, K,
                                             _ptr(y_shared), _ptr(y), _stream()))
     return y
+
+
+def place_experts(Cm, n_dev):
+    """Sec. 3.4: greedy co-location of collaborating experts.  Returns int32[E] expert -> device."""
+    E = Cm.shape[0]
+    out = torch.empty((E,), dtype=torch.int32, device=Cm.device)
+    _check("c2r_place_experts", lib().c2r_place_experts(_ptr(Cm), E, n_dev, _ptr(out), _stream()))
+    return out
 
 
 def dedup_dispatch(topk_idx, E, expert_device, n_dev, ws=None):

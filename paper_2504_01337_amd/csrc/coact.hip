@@ -98,9 +98,57 @@ __global__ __launch_bounds__(64) void collaborators_kernel(const int32_t *__rest
     if (collab_mask && j == 0) collab_mask[i] = bal;
 }
 
+// Greedy co-location of collaborating experts (Sec. 3.4), one wave, lane = expert.  Devices
+// are filled in order with ceil(E / n_dev) experts each: a device starts with the unplaced
+// expert whose row of C (diagonal left out) sums highest and then keeps taking the unplaced
+// expert with the largest total co-activation with its members; ties go to the lower index.
+// The row of C sits in LDS; each step is a masked row sum per lane and a wave-wide arg max.
+__global__ __launch_bounds__(64) void place_experts_kernel(const int32_t *__restrict__ C, int E, int n_dev,
+                                                           int32_t *__restrict__ expert_device) {
+    __shared__ int32_t Cl[C2R_MAX_E][C2R_MAX_E + 1];
+    const int e = threadIdx.x;
+    for (int i = e; i < E * E; i += 64) Cl[i / E][i % E] = C[i];
+    __syncthreads();
+    const int cap = (E + n_dev - 1) / n_dev;
+    uint64_t placed = 0;  // wave-uniform
+    int mine = -1;
+    for (int g = 0; g < n_dev; ++g) {
+        uint64_t members = 0;
+        for (int m = 0; m < cap; ++m) {
+            const bool free_lane = e < E && !((placed >> e) & 1ull);
+            long long score = 0;
+            if (free_lane)
+                for (int j = 0; j < E; ++j)
+                    if (j != e && (members == 0 || ((members >> j) & 1ull))) score += Cl[e][j];
+            // arg max over the free lanes, lower index on ties: the largest score first ...
+            long long best = free_lane ? score : -1;  // scores are sums of counts, never negative
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) {
+                const long long o = __shfl_xor(best, off);
+                best = o > best ? o : best;
+            }
+            const uint64_t cand = __ballot(free_lane && score == best);
+            if (cand == 0) break;  // everything is placed
+            const int pick = __ffsll((unsigned long long)cand) - 1;
+            if (e == pick) mine = g;
+            placed |= 1ull << pick;
+            members |= 1ull << pick;
+        }
+    }
+    if (e < E) expert_device[e] = mine;
+}
+
 }  // namespace c2r
 
 using namespace c2r;
+
+extern "C" int c2r_place_experts(const int32_t *C, int E, int n_dev, int32_t *expert_device, void *stream) {
+    if (E < 1 || n_dev < 1) return C2R_ERR_INVALID_ARG;
+    if (E > C2R_MAX_E || n_dev > C2R_MAX_E) return C2R_ERR_UNSUPPORTED;
+    if (!C || !expert_device) return C2R_ERR_INVALID_ARG;
+    place_experts_kernel<<<dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream)>>>(C, E, n_dev, expert_device);
+    return launch_status();
+}
 
 extern "C" int c2r_build_coactivation(const int32_t *topk_idx, int64_t T, int K, int E, int32_t *C,
                                       void *stream) {

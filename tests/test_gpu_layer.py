@@ -70,6 +70,7 @@ def _run_layer(c2r, orc, w, n_sample):
     print(f"[layer] {w.name} max rel err {err:.3e} (bar {TOL[w.dtype]})", flush=True)
     assert err <= TOL[w.dtype]
     assert torch.isfinite(y.float()).all()
+    layer.Cm = Cm
     return layer, o
 
 
@@ -92,6 +93,7 @@ def test_layer_full_size(c2r, orc, name):
         # (bit exact), its copy count against the host-side count of distinct devices, and the
         # two-level combine against the layer's own output
         dm = wl.device_map(w.E, 4)
+        Cm = layer.Cm
         counts, offsets, tok, row = c2r.dedup_dispatch(layer.idx, w.E, dev(dm), 4)
         rc, ro, rt, rr = orc.dedup_dispatch(o.idx, w.E, dm, 4)
         n = int(ro[-1])
@@ -102,6 +104,15 @@ def test_layer_full_size(c2r, orc, name):
         print("[layer] %s copies sent per token (4 devices): C2R %.3f, top-K %.3f; redundancy %.3f vs %.3f" % (
             name, dd.mean(), orc.distinct_devices(idx_topk, dm).mean(), orc.redundancy(dd, w.K),
             orc.redundancy(orc.distinct_devices(idx_topk, dm), w.K)), flush=True)
+        # the same with experts co-located by their profiled co-activation (Sec. 3.4)
+        placed = c2r.place_experts(Cm, 4)
+        pm = orc.place_experts(o.C, 4)
+        assert np.array_equal(host(placed), pm)
+        _, poff, _, _ = c2r.dedup_dispatch(layer.idx, w.E, placed, 4)
+        pd, pdk = orc.distinct_devices(o.idx, pm), orc.distinct_devices(idx_topk, pm)
+        assert int(poff[-1].item()) == int(pd.sum())
+        print("[layer] %s with co-located experts: C2R %.3f copies/token (redundancy %.3f), top-K %.3f (%.3f)" % (
+            name, pd.mean(), orc.redundancy(pd, w.K), pdk.mean(), orc.redundancy(pdk, w.K)), flush=True)
         part = c2r.combine_partial(layer.y_perm, layer.gates, layer.inv_perm, tok, row, offsets)
         y2 = c2r.combine_copies(part, row, w.T, w.K, layer.y_shared)
         torch.cuda.synchronize()

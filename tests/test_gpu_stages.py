@@ -330,3 +330,25 @@ def test_two_level_combine(c2r, orc, dtype, T, K, d, n_dev):
         # and exactly the second level applied to the first level's (rounded) rows
         ref2 = orc.combine_copies(host(part)[:n], rr, T, K, shared)
         assert np.abs(host(y) - ref2).max() <= tol * max(np.abs(ref2).max(), 1.0)
+
+
+@pytest.mark.parametrize("E,n_dev,kind", [(12, 4, "blocks"), (60, 4, "random"), (64, 8, "random"), (10, 4, "ties"),
+                                          (7, 7, "random"), (60, 6, "profile")])
+def test_place_experts(c2r, orc, E, n_dev, kind):
+    rng = np.random.default_rng(E + n_dev)
+    if kind == "blocks":
+        label = rng.permutation(np.repeat(np.arange(n_dev), E // n_dev))
+        Cm = (label[:, None] == label[None, :]).astype(np.int64) * 100 + rng.integers(0, 10, size=(E, E))
+        Cm = Cm + Cm.T
+    elif kind == "ties":
+        Cm = np.ones((E, E), dtype=np.int64)
+    elif kind == "profile":
+        w = wl.WORKLOADS["C3"]
+        Wg, b = wl.router(w)
+        idx, _ = orc.route(orc.logits_canon_f32(wl.hidden(w, 4096, stream=1), Wg, b), w.K)
+        Cm = orc.coactivation(idx, w.E)
+    else:
+        Cm = rng.integers(0, 1000, size=(E, E))
+        Cm = Cm + Cm.T
+    got = c2r.place_experts(dev(Cm.astype(np.int32)), n_dev)
+    assert np.array_equal(host(got), orc.place_experts(Cm, n_dev))
