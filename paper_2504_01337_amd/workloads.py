@@ -58,6 +58,10 @@ WORKLOADS = {
     "C4": Workload("C4", T=1048576, d=2048, E=60, F=0, K=4, Tc=16, dtype="f32", groups=6, cfg_id=4),
     "C5": Workload("C5", T=32768, d=2048, E=60, F=1408, K=4, Tc=16, dtype="bf16", groups=6,
                    zipf=True, E_local=15, T_profile=65536, cfg_id=5),
+    # the paper's own LLaMA-MoE setting (Sec. 4.1: 8 experts, top-2, intermediate width 1376,
+    # collaborator lists of 5), as a second shape for the list-length sweep of Fig. 3
+    "L1": Workload("L1", T=2048, d=4096, E=8, F=1376, K=2, Tc=5, dtype="bf16", groups=2,
+                   T_profile=8192, cfg_id=6),
 }
 
 

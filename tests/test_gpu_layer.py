@@ -120,6 +120,29 @@ def test_layer_full_size(c2r, orc, name):
         assert np.abs(host(y2) - ref).max() <= 2.0 ** -7 * np.abs(ref).max()   # one more rounding than c2r_combine
 
 
+def test_layer_llama_moe_shape_and_list_length_sweep(c2r, orc):
+    """The paper's LLaMA-MoE setting (Sec. 4.1) end to end, then Fig. 3's axes on the same
+    kernels: collaborator lists of every length 1..E-1 (E-1 = conventional top-K) and the
+    random-list variant, routing compared bit for bit."""
+    w = wl.WORKLOADS["L1"]
+    layer, o = _run_layer(c2r, orc, w, n_sample=64)
+    x, Wg, bias = dev(o.x, w.dtype), dev(o.Wg), dev(o.bias)
+    topk, gk = orc.route(o.logits, w.K)
+    rng = np.random.default_rng(61)
+    for Tc in range(1, w.E):
+        lists = orc.collaborators(o.C, Tc)
+        rand = np.stack([rng.permutation([j for j in range(w.E) if j != i])[:Tc] for i in range(w.E)]).astype(np.int32)
+        for ci in (lists, rand):
+            idx, g, _ = c2r.route(x, Wg, bias, w.K, dev(ci))
+            ri, rg = orc.route(o.logits, w.K, ci)
+            assert np.array_equal(host(idx), ri), Tc
+            np.testing.assert_allclose(host(g), rg, rtol=2e-6, atol=1e-7)
+            if Tc == 1:                                    # Fig. 3, T = 1: the partner is the list entry
+                assert np.array_equal(ri[:, 1], ci[ri[:, 0], 0])
+            if Tc == w.E - 1:                              # Fig. 3 caption: degenerates to top-K
+                assert np.array_equal(ri, topk)
+
+
 def test_profiling_c4_full_size(c2r, orc):
     # 2^20 tokens: stored fp32 logits -> top-4 -> co-activation counts -> top-16 lists
     w = wl.WORKLOADS["C4"]
