@@ -217,6 +217,21 @@ def main():
             stage_info[name] = {"ms": st_ms[name], "TFLOPs": tf, "frac_mfma": tf / PEAK["mfma_bf16_TFLOPs"]}
     if not L.overlap:
         ffn_span_ms = sum(st_ms.get(k, 0.0) for k in ("ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down"))
+    # Group-wise roof of the routed passes: an expert with few rows is bound by streaming its
+    # weights, not by the matrix pipe, so the launch's floor is the sum over experts of
+    # max(flops / MFMA peak, bytes / HBM peak) with each group given the whole chip.
+    cnts = L.counts.cpu().numpy().astype(np.float64)
+    peak_fl = (PEAK["mfma_bf16_TFLOPs"] if w.dtype == "bf16" else PEAK["valu_f32_TFLOPs"]) * 1e12
+    hbm = PEAK["hbm_GBps"] * 1e9
+    nz = cnts > 0
+    t_gu = np.maximum(4.0 * cnts * w.d * w.F / peak_fl, (2.0 * w.F * w.d + cnts * (w.d + w.F)) * sz / hbm)[nz].sum()
+    t_dn = np.maximum(2.0 * cnts * w.d * w.F / peak_fl, (1.0 * w.F * w.d + cnts * (w.d + w.F)) * sz / hbm)[nz].sum()
+    for name, t in (("ffn_gate_up", t_gu), ("ffn_down", t_dn)):
+        if name in stage_info:
+            stage_info[name]["groupwise_roof_ms"] = t * 1e3
+            stage_info[name]["frac_groupwise_roof"] = t * 1e3 / st_ms[name]
+            stage_info[name]["groups_weight_bound"] = int((nz & (4.0 * cnts * w.d * w.F / peak_fl <
+                                                                 (2.0 * w.F * w.d + cnts * (w.d + w.F)) * sz / hbm)).sum())
     ffn_tf = (fl_gu + fl_dn + fl_sgu + fl_sdn) / ffn_span_ms / 1e9
     stage_info["expert_ffn_all"] = {"ms": ffn_span_ms, "TFLOPs": ffn_tf, "frac_mfma": ffn_tf / PEAK["mfma_bf16_TFLOPs"],
                                     "note": "first FFN launch's start to last one's end; route and permute run inside it"
