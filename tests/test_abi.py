@@ -63,6 +63,19 @@ def test_argument_errors_before_launch():
     assert L.c2r_expert_ffn(p, 1, p, 4, 64, 64, 64, p, p, p, p, null, 0, null) == c2r.ERR_WORKSPACE
     assert L.c2r_combine(p, 1, p, p, 16, 60, 2, null, p, null) == c2r.ERR_UNSUPPORTED
     assert L.c2r_combine(null, 1, p, p, 16, 64, 2, null, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_expert_ffn_gate_up_gather(p, 0, p, 16, 2, p, 4, 32, 64, 64, p, p, p, null) == c2r.ERR_UNSUPPORTED  # fp32
+    assert L.c2r_expert_ffn_gate_up_gather(p, 1, null, 16, 2, p, 4, 32, 64, 64, p, p, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_place_experts(p, 65, 4, p, null) == c2r.ERR_UNSUPPORTED
+    assert L.c2r_place_experts(null, 8, 4, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_place_experts(p, 8, 0, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_dedup_dispatch(p, 16, 2, 8, p, 65, p, p, p, p, p, 1 << 20, null) == c2r.ERR_UNSUPPORTED
+    assert L.c2r_dedup_dispatch(p, 16, 2, 8, null, 4, p, p, p, p, p, 1 << 20, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_dedup_dispatch(p, 16, 2, 8, p, 4, p, p, p, p, null, 0, null) == c2r.ERR_WORKSPACE
+    assert L.c2r_combine_partial(p, 1, p, p, p, p, p, 16, 32, 60, 2, p, null) == c2r.ERR_UNSUPPORTED
+    assert L.c2r_combine_partial(p, 1, p, p, p, p, null, 16, 32, 64, 2, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_combine_copies(p, 1, null, 16, 32, 64, 2, null, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_probe_mfma_bf16(p, 0, 4, p, None, null) == c2r.ERR_INVALID_ARG
+    assert c2r.workspace_bytes(c2r.STAGE_DEDUP_DISPATCH, 5000, 0, 4, 4, 0, c2r.F32) == 256
     # empty batches are fine and launch nothing
     assert L.c2r_route(null, 1, null, null, 0, 64, 8, 2, null, 0, null, null, null, null, 0, null) == c2r.OK
     assert L.c2r_combine(null, 1, null, null, 0, 64, 2, null, null, null) == c2r.OK

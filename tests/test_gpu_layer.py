@@ -159,3 +159,39 @@ def test_profiling_c4_full_size(c2r, orc):
     assert np.array_equal(host(collab), orc.collaborators(C_ref, w.Tc))
     sel = np.random.default_rng(4).permutation(w.T)[:4096]
     np.testing.assert_allclose(host(gates)[sel], g_ref[sel], rtol=2e-6, atol=1e-7)
+
+
+def test_layer_forward_in_a_captured_graph(c2r, orc):
+    """The library allocates nothing, synchronises nothing and records no memset: a forward
+    captured in a graph replays to the eager result, every time, with eager work in between."""
+    w = wl.scaled(wl.WORKLOADS["C3"], T=1024, T_profile=2048)
+    o = OracleLayer(orc, w)
+    wg, wu, wd = wl.expert_weights(w)
+    shared = wl.shared_expert_weights(w)
+    layer = c2r.C2RLayer(w.T, w.d, w.E, w.K, w.F, torch.bfloat16, dev(o.Wg), dev(o.bias), dev(o.collab),
+                         dev(wg, "bf16"), dev(wu, "bf16"), dev(wd, "bf16"), local_slot=dev(o.local_slot),
+                         E_local=w.n_local, shared=tuple(dev(a, "bf16") for a in shared))
+    x = dev(o.x, "bf16")
+    y_eager = layer.forward(x).clone()
+    idx_eager = layer.idx.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        layer.forward(x)                                   # warm-up on the capture stream
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            layer.forward(x)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for i in range(4):
+        layer.y.zero_()
+        layer.idx.fill_(-7)
+        layer.h.fill_(float("nan"))                       # stale scratch must not leak into a replay
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(layer.idx, idx_eager), i
+        assert torch.equal(layer.y, y_eager), i
+        y2 = layer.forward(x)                              # eager work between the replays
+        torch.cuda.synchronize()
+        assert torch.equal(y2, y_eager)
