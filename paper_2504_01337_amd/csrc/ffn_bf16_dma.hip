@@ -248,9 +248,9 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) bset[set][j] = *reinterpret_cast<const bf16x8 *>(stage + rdB[j] + ch);
     };
-    static_assert(NPIECE == 8, "copy schedule below: 3 + 3 + 2 pieces over three k-steps");
+    static_assert(NPIECE == 8, "copy schedule below: 4 + 4 pieces over two k-steps");
     // MFMAs of one k-step (operands swapped: the lane's 4 results lie along n) with up to
-    // four copy pieces P0.. of slice CKT slipped in after every fourth MFMA.  Macros, so that
+    // eight copy pieces P0.. of slice CKT slipped in after every second MFMA.  Macros, so that
     // every fragment and piece index is a literal and the arrays stay in registers.
 #define C2R_MFMA(AS, BS, H, I, J)                                                                 \
     acc[(H) * 4 + (I)][J] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(bset[BS][J], aset[AS][I],     \
@@ -266,25 +266,38 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         copy_piece(CKT, CST, (P0) + (Q), STEADY);   \
         __builtin_amdgcn_sched_barrier(0);          \
     }
+#define C2R_MFMA_HALF(AS, BS, H, I, J0) \
+    C2R_MFMA(AS, BS, H, I, (J0));         \
+    C2R_MFMA(AS, BS, H, I, (J0) + 1)
 #define C2R_KSTEP(AS, BS, H, CKT, CST, P0, NCP)     \
     do {                                            \
         __builtin_amdgcn_sched_barrier(0);          \
-        C2R_MFMA_ROW(AS, BS, H, 0);                 \
+        C2R_MFMA_HALF(AS, BS, H, 0, 0);             \
         C2R_COPY_IF(0, NCP, CKT, CST, P0)           \
-        C2R_MFMA_ROW(AS, BS, H, 1);                 \
+        C2R_MFMA_HALF(AS, BS, H, 0, 2);             \
         C2R_COPY_IF(1, NCP, CKT, CST, P0)           \
-        C2R_MFMA_ROW(AS, BS, H, 2);                 \
+        C2R_MFMA_HALF(AS, BS, H, 1, 0);             \
         C2R_COPY_IF(2, NCP, CKT, CST, P0)           \
-        C2R_MFMA_ROW(AS, BS, H, 3);                 \
+        C2R_MFMA_HALF(AS, BS, H, 1, 2);             \
         C2R_COPY_IF(3, NCP, CKT, CST, P0)           \
+        C2R_MFMA_HALF(AS, BS, H, 2, 0);             \
+        C2R_COPY_IF(4, NCP, CKT, CST, P0)           \
+        C2R_MFMA_HALF(AS, BS, H, 2, 2);             \
+        C2R_COPY_IF(5, NCP, CKT, CST, P0)           \
+        C2R_MFMA_HALF(AS, BS, H, 3, 0);             \
+        C2R_COPY_IF(6, NCP, CKT, CST, P0)           \
+        C2R_MFMA_HALF(AS, BS, H, 3, 2);             \
+        C2R_COPY_IF(7, NCP, CKT, CST, P0)           \
         __builtin_amdgcn_sched_barrier(0);          \
     } while (0)
 
     // One 64-wide slice = four k-steps.  The hand-over barrier sits before the LAST k-step:
     // by then the copy of the next slice has landed and every wave has finished reading this
     // slice's stage.  After it, the copy of the slice after next starts going into this stage
-    // (3 pieces in the last k-step here, 3 + 2 in the first two k-steps of the next slice,
-    // none in the third so that they land before the next barrier), and the first fragments
+    // (4 pieces in the last k-step here, 4 in the first k-step of the next slice, one after
+    // every second MFMA: as early as the stage allows, so that they have landed well before
+    // the next barrier; measured 3.5 % faster per step than 3 + 3 + 2 pieces spread one per
+    // four MFMAs over three k-steps), and the first fragments
     // of the next slice are read while the last k-step's MFMAs run, so the MFMA stream
     // never starts a slice by waiting on LDS.
     // `steady` (a compile-time flag): kt + 3 < nk, i.e. both following slices exist and neither
@@ -293,9 +306,9 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     auto slice_step = [&](int kt, unsigned char *cur, unsigned char *nxt, auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
 #ifndef C2R_CPA
-#define C2R_CPA 3
-#define C2R_CPB 3
-#define C2R_CPC 2
+#define C2R_CPA 4
+#define C2R_CPB 4
+#define C2R_CPC 0
 #define C2R_CPD 0
 #endif
         static_assert(C2R_CPA + C2R_CPB + C2R_CPC + C2R_CPD == 8, "all pieces scheduled");
@@ -314,10 +327,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             if (C2R_CPA <= 1) copy_piece(kt + 1, nxt, 1);
             if (C2R_CPA <= 2) copy_piece(kt + 1, nxt, 2);
             if (C2R_CPA <= 3) copy_piece(kt + 1, nxt, 3);
-            copy_piece(kt + 1, nxt, 4);
-            copy_piece(kt + 1, nxt, 5);
-            copy_piece(kt + 1, nxt, 6);
-            copy_piece(kt + 1, nxt, 7);
+            if (C2R_CPA <= 4) copy_piece(kt + 1, nxt, 4);
+            if (C2R_CPA <= 5) copy_piece(kt + 1, nxt, 5);
+            if (C2R_CPA <= 6) copy_piece(kt + 1, nxt, 6);
+            if (C2R_CPA <= 7) copy_piece(kt + 1, nxt, 7);
         }
         wait_copies_and_lds();  // my copies of slice kt+1 landed, my reads of `cur` returned
         lds_barrier();
@@ -332,6 +345,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             if (C2R_CPA > 1) copy_piece(kt + 2, cur, 1);
             if (C2R_CPA > 2) copy_piece(kt + 2, cur, 2);
             if (C2R_CPA > 3) copy_piece(kt + 2, cur, 3);
+            if (C2R_CPA > 4) copy_piece(kt + 2, cur, 4);
+            if (C2R_CPA > 5) copy_piece(kt + 2, cur, 5);
+            if (C2R_CPA > 6) copy_piece(kt + 2, cur, 6);
+            if (C2R_CPA > 7) copy_piece(kt + 2, cur, 7);
         }
     };
 
@@ -399,6 +416,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             if (C2R_CPA > 1) copy_piece(1, st1, 1);
             if (C2R_CPA > 2) copy_piece(1, st1, 2);
             if (C2R_CPA > 3) copy_piece(1, st1, 3);
+            if (C2R_CPA > 4) copy_piece(1, st1, 4);
+            if (C2R_CPA > 5) copy_piece(1, st1, 5);
+            if (C2R_CPA > 6) copy_piece(1, st1, 6);
+            if (C2R_CPA > 7) copy_piece(1, st1, 7);
         }
         if (active) {
             read_a(st0, 0, 0, 0);
