@@ -4,6 +4,21 @@
 
 namespace c2r {
 
+// Inclusive prefix sum over the 64 lanes of a wave with data-parallel-primitive moves (no
+// LDS round trips): shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the row totals
+// are passed on with the two row broadcasts.  Every lane must be active.
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, true);  // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, true);  // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, true);  // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, true);  // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);  // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);  // row_bcast:31 into rows 2, 3
+#endif
+    return v;
+}
+
 struct GroupTile {
     int expert;        // local expert slot, -1: no such tile
     int row_begin;     // first row of the tile in x_perm
@@ -38,12 +53,7 @@ __device__ __forceinline__ GroupMap build_group_map(const int32_t *__restrict__ 
     }
     const int cnt = m.hi - m.lo;
     m.tiles = (cnt + BM - 1) / BM;
-    int incl = m.tiles;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int v = __shfl_up(incl, off);
-        if (lane >= off) incl += v;
-    }
+    const int incl = wave_inclusive_scan(m.tiles);
     m.first = incl - m.tiles;
     m.total_mtiles = __shfl(incl, 63);
     return m;
@@ -173,13 +183,7 @@ __device__ __forceinline__ RaggedMap build_ragged_map(const int32_t *__restrict_
     const int cnt = gm.hi - gm.lo;
     const bool short_last = gm.tiles > 0 && cnt - (gm.tiles - 1) * BM <= BM / 2;
     m.cost = 2 * gm.tiles - (short_last ? 1 : 0);
-    const int lane = lane_id();
-    int incl = m.cost;
-#pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const int v = __shfl_up(incl, off);
-        if (lane >= off) incl += v;
-    }
+    const int incl = wave_inclusive_scan(m.cost);
     m.pcost = incl - m.cost;
     m.total_cost = __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
     return m;
