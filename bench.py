@@ -248,13 +248,25 @@ def main():
     n_launch = 2 if shared else 1
     dom_ms = sum(dom_ms_live.values()) / n_launch   # from the timed region
     dom_fl = (fl_gu + fl_sgu) / n_launch
+    both = ""
+    # where the intermediate width is not a multiple of 64 the layer calls c2r_expert_ffn, whose
+    # two passes are not bracketed separately: the events then span both kernels of a call
+    if not L.fuse_gather:
+        dom_fl += fl_dn / n_launch
+    if shared and not L.split_shared:
+        dom_fl += fl_sdn / n_launch
+    if not L.fuse_gather:
+        both = " and <1> (both passes of c2r_expert_ffn)"
+        for k_gu, k_dn in (("ffn_gate_up", "ffn_down"), ("shared_gate_up", "shared_down")):
+            if k_gu in stage_info and k_dn in stage_info:
+                stage_info[k_gu]["note"] = "both passes (c2r_expert_ffn); flops of gate/up only in TFLOPs"
     if w.dtype == "bf16":
-        roofline = {"kernel": "ffn_bf16_dma_kernel<0> (gate/up + SwiGLU)", "bound": "mfma",
+        roofline = {"kernel": "ffn_bf16_dma_kernel<0>" + both + " (gate/up + SwiGLU)", "bound": "mfma",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["mfma_bf16_TFLOPs"], "unit": "TFLOP/s",
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["mfma_bf16_TFLOPs"], "traffic": traffic,
                     "avg_launch_ms": dom_ms, "launches_per_step": n_launch}
     else:
-        roofline = {"kernel": "ffn_f32_kernel<0> (gate/up + SwiGLU)", "bound": "alu",
+        roofline = {"kernel": "ffn_f32_kernel<0>" + both + " (gate/up + SwiGLU)", "bound": "alu",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["valu_f32_TFLOPs"], "unit": "TFLOP/s",
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["valu_f32_TFLOPs"], "traffic": None,
                     "avg_launch_ms": dom_ms, "launches_per_step": n_launch}
