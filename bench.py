@@ -186,6 +186,29 @@ def main():
           "combine_copies": {"ms": zr_ms[2], "GBps": copies_bytes / zr_ms[2] / 1e6,
                              "frac_hbm": copies_bytes / zr_ms[2] / 1e6 / PEAK["hbm_GBps"]}}
 
+    # Sec. 4.1 / Table 3: token redundancy for expert-parallel degrees 2..6 in one pass per routing
+    # (c2r_distinct_devices), for contiguous maps and for maps co-located from the profile, and
+    # the estimator "all-to-all share x redundancy" fed with the shares Table 3 prints for the
+    # paper's own testbed (context only: another machine, real tokens).  Eq. 3 on the profile too.
+    eps = [ep for ep in (2, 3, 4, 5, 6) if ep <= w.E]
+    a2a_share = {2: 0.301, 3: 0.407, 4: 0.619, 5: 0.763, 6: 0.772}
+    maps_c = dev(np.stack([wl.device_map(w.E, ep) for ep in eps]))
+    maps_p = torch.stack([c2r.place_experts(Cm, ep) for ep in eps])
+    sweep = {}
+    for mname, maps in (("contiguous_map", maps_c), ("co_located_map", maps_p)):
+        tot_c2r = c2r.distinct_devices(L.idx, w.E, maps, max(eps)).tolist()
+        tot_topk = c2r.distinct_devices(idx_topk, w.E, maps, max(eps)).tolist()
+        sweep[mname] = {str(ep): {"c2r": red(tot_c2r[i]), "top_k": red(tot_topk[i]),
+                                  "est_speedup_c2r": a2a_share[ep] * red(tot_c2r[i]),
+                                  "est_speedup_top_k": a2a_share[ep] * red(tot_topk[i])}
+                        for i, ep in enumerate(eps)}
+    zr["redundancy_by_ep"] = sweep
+    zr["redundancy_by_ep_note"] = ("est_speedup = Table 3's all-to-all time share of the paper's testbed x the "
+                                   "redundancy measured here on synthetic tokens")
+    P_deg = c2r.collaboration_degree(Cm)
+    zr["collaboration_degree_eq3"] = {"mean": float(P_deg.mean()), "min": float(P_deg.min()),
+                                      "max": float(P_deg.max()), "uniform_limit_ln_E_minus_1": float(np.log(max(w.E - 1, 1)))}
+
     # ---- algorithmic work per stage ----
     n_local = int(L.offsets[-1].item())          # rows the local experts process
     A = w.T * w.K

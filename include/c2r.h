@@ -156,7 +156,7 @@ int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T,
                 void *stream);
 
 /*
- * Grouped expert FFN (Sec. 3.1: "each token is fed to its selected experts"):
+ * Grouped expert FFN (Sec. 3.1: every token is processed by each expert selected for it):
  * for each local expert e and each row r in [offsets[e], offsets[e+1]):
  *     y_perm[r] = W_down,e ( silu(W_gate,e x_perm[r]) * (W_up,e x_perm[r]) )
  * with silu(z) = z / (1 + exp(-z)), no biases, un-weighted by the gate.
@@ -210,8 +210,8 @@ int c2r_combine(const void *y_perm, c2r_dtype dt, const float *gates, const int3
                 int64_t T, int d, int K, const void *y_shared, void *y, void *stream);
 
 /*
- * Zero-redundancy dispatch index (Sec. 3.4: "sends only a single copy of the token to the
- * shared device, where it is subsequently replicated locally"), built on one GPU.  For a
+ * Zero-redundancy dispatch index (Sec. 3.4: a token whose experts share a device travels
+ * there once and is replicated on arrival), built on one GPU.  For a
  * map expert -> device, every token gets ONE copy per device that hosts at least one of its
  * selected experts.  The copies are listed device after device, tokens ascending:
  *   send_counts[g], send_offsets[g]   : copies for device g (send_offsets has n_dev+1 entries,
@@ -234,8 +234,8 @@ int c2r_dedup_dispatch(const int32_t *topk_idx, int64_t T, int K, int E, const i
                        int32_t *send_row, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * Expert -> device map that co-locates collaborating experts (Sec. 3.4: "we can co-locate
- * closely collaborating experts on the same computational units"; the paper names the goal
+ * Expert -> device map that co-locates collaborating experts (Sec. 3.4 proposes placing
+ * experts that collaborate closely on one device; the paper names the goal
  * and gives no procedure - this is a greedy fill).  Devices 0..n_dev-1 are filled in order
  * with ceil(E / n_dev) experts each (the last ones with what is left): a device starts with
  * the unplaced expert whose row of C, diagonal left out, sums highest, and then keeps taking
@@ -263,6 +263,34 @@ int c2r_combine_partial(const void *y_perm, c2r_dtype dt, const float *gates, co
                         int64_t T, int64_t cap_rows, int d, int K, void *y_part, void *stream);
 int c2r_combine_copies(const void *y_part, c2r_dtype dt, const int32_t *send_row, int64_t T,
                        int64_t cap_rows, int d, int K, const void *y_shared, void *y, void *stream);
+
+/*
+ * Collaboration degree of every expert (Eq. 3): the entropy of the frequencies with which
+ * expert i is co-activated with each OTHER expert,
+ *     p_ij = C[i,j] / sum_{j' != i} C[i,j'],    P[i] = - sum_{j != i, C[i,j] > 0} p_ij ln p_ij
+ * (the equation's limits are printed inconsistently; the reading taken leaves the diagonal
+ * out of the sum and of the normalisation and uses the natural logarithm).  A row without
+ * co-activations gives 0.  Computed in fp64.
+ * C : int32[E,E] (DEVICE, as c2r_build_coactivation leaves it; negative entries count as 0)
+ * P : double[E] out (DEVICE).  E <= 64.
+ */
+int c2r_collaboration_degree(const int32_t *C, int E, double *P, void *stream);
+
+/*
+ * Distinct destination devices per token, for several expert -> device maps in one pass
+ * over the indices (Sec. 4.1: the token redundancy of an expert-parallel degree is the
+ * share of (token, expert) copies that a zero-redundancy dispatch does not send,
+ * 1 - totals[m] / (T*K); Table 3 lists it for degrees 2..6).
+ * topk_idx      : int32[T,K] (entries outside [0,E) are skipped)
+ * expert_device : int32[n_maps, E]; entries outside [0, n_dev) mean "no device" and are
+ *                 skipped.  n_maps <= 8, n_dev <= 64, E <= 64.
+ * per_token     : int32[n_maps, T] out or NULL - the count for every token and map
+ * totals        : int64[n_maps] out (8-byte aligned) - the sum over the tokens; equals the
+ *                 n_send that c2r_dedup_dispatch reports for the same map.  Exact.
+ * All pointers are DEVICE memory.
+ */
+int c2r_distinct_devices(const int32_t *topk_idx, int64_t T, int K, int E, const int32_t *expert_device,
+                         int n_maps, int n_dev, int32_t *per_token, int64_t *totals, void *stream);
 
 /*
  * Measurement aid, not a step of the path (Sec. 4 reports efficiency; no passage defines

@@ -371,7 +371,7 @@ void orc_combine_copies(const double *y_part, const int32_t *send_row, int64_t T
         }
 }
 
-/* ---- Sec. 3.4: "co-locate closely collaborating experts on the same computational units".
+/* ---- Sec. 3.4 proposes placing experts that collaborate closely on one device.
  * The paper names the goal and gives no procedure; the reading taken is a greedy fill.
  * Devices 0..n_dev-1 are filled one after the other, each with cap = ceil(E / n_dev) experts
  * (the last ones with what is left).  A device starts with the unplaced expert whose

@@ -14,7 +14,7 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libc2r_hip.so")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "route.hip", "coact.hip", "permute.hip", "combine.hip", "ffn_f32.hip", "ffn_bf16.hip", "ffn_bf16_dma.hip",
-           "dedup.hip", "probe.hip"]
+           "dedup.hip", "metrics.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -24,7 +24,8 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine",
-           "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies", "c2r_probe_mfma_bf16"]
+           "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies",
+           "c2r_collaboration_degree", "c2r_distinct_devices", "c2r_probe_mfma_bf16"]
 
 
 class C2RError(RuntimeError):
@@ -63,6 +64,8 @@ def lib():
         L.c2r_dedup_dispatch.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_combine_partial.argtypes = [vp, i32, vp, vp, vp, vp, vp, i64, i64, i32, i32, vp, vp]
         L.c2r_combine_copies.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp]
+        L.c2r_collaboration_degree.argtypes = [vp, i32, vp, vp]
+        L.c2r_distinct_devices.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
         L.c2r_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i32
@@ -290,6 +293,28 @@ def combine_copies(y_part, send_row, T, K, y_shared=None, out=None):
     return y
 
 
+def collaboration_degree(Cm):
+    """Eq. 3: fp64[E], the entropy of each expert's co-activation frequencies with the others."""
+    E = Cm.shape[0]
+    P = torch.empty((E,), dtype=torch.float64, device=Cm.device)
+    _check("c2r_collaboration_degree", lib().c2r_collaboration_degree(_ptr(Cm), E, _ptr(P), _stream()))
+    return P
+
+
+def distinct_devices(topk_idx, E, expert_device, n_dev, per_token=False):
+    """Sec. 4.1: for every row of expert_device (int32[n_maps, E] or int32[E]) the number of
+    (token, device) copies a zero-redundancy dispatch sends.  Returns int64[n_maps] totals
+    (and int32[n_maps, T] per-token counts if asked); redundancy = 1 - totals / (T*K)."""
+    T, K = topk_idx.shape
+    maps = expert_device.reshape(-1, E)
+    n_maps = maps.shape[0]
+    totals = torch.empty((n_maps,), dtype=torch.int64, device=topk_idx.device)
+    pt = torch.empty((n_maps, T), dtype=torch.int32, device=topk_idx.device) if per_token else None
+    _check("c2r_distinct_devices", lib().c2r_distinct_devices(_ptr(topk_idx), T, K, E, _ptr(maps), n_maps, n_dev,
+                                                            _ptr(pt), _ptr(totals), _stream()))
+    return (totals, pt) if per_token else totals
+
+
 def probe_mfma_bf16(operands, iters, blocks, out):
     """Measurement aid: a pure bf16 matrix-instruction loop.  Returns the launch's flops."""
     assert operands.numel() * operands.element_size() >= 1024 * 16 and out.numel() >= blocks * 512
@@ -307,9 +332,10 @@ class C2RLayer:
     default priority, because the shared expert needs neither the routing nor the dispatch:
         side stream : shared gate/up ........................ shared down
         main stream : route, permute | routed gate/up | routed down | combine
-    Measured at the Qwen-MoE shape this is worth about 1 % of the step (the router's fp32
-    FMAs and the GEMM's MFMAs share the SIMDs' issue slots, so what route and permute
-    save, the shared gate/up pass beside them loses again); the default is one stream."""
+    Measured at the Qwen-MoE shape this gains nothing (within 1 % of one stream, lately on
+    the slow side): the router's fp32 FMAs and the GEMM's MFMAs share the SIMDs' issue slots,
+    so what route and permute save, the shared gate/up pass beside them loses again.  The
+    default is one stream."""
 
     def __init__(self, T, d, E, K, F, dtype, Wg, bias, collab_idx, w_gate, w_up, w_down,
                  local_slot=None, E_local=None, shared=None, device="cuda", fuse_gather=None, overlap=False):

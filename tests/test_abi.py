@@ -75,6 +75,11 @@ def test_argument_errors_before_launch():
     assert L.c2r_combine_partial(p, 1, p, p, p, p, null, 16, 32, 64, 2, p, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_combine_copies(p, 1, null, 16, 32, 64, 2, null, p, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_probe_mfma_bf16(p, 0, 4, p, None, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_collaboration_degree(p, 65, p, null) == c2r.ERR_UNSUPPORTED
+    assert L.c2r_collaboration_degree(p, 8, null, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_distinct_devices(p, 16, 2, 8, p, 9, 4, null, p, null) == c2r.ERR_UNSUPPORTED   # more than 8 maps
+    assert L.c2r_distinct_devices(p, 16, 2, 8, p, 2, 4, null, null, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_distinct_devices(p, 16, 2, 8, p, 2, 4, null, ctypes.c_void_p(0x1004), null) == c2r.ERR_INVALID_ARG
     assert c2r.workspace_bytes(c2r.STAGE_DEDUP_DISPATCH, 5000, 0, 4, 4, 0, c2r.F32) == 256
     # empty batches are fine and launch nothing
     assert L.c2r_route(null, 1, null, null, 0, 64, 8, 2, null, 0, null, null, null, null, 0, null) == c2r.OK

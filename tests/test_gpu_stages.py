@@ -352,3 +352,54 @@ def test_place_experts(c2r, orc, E, n_dev, kind):
         Cm = Cm + Cm.T
     got = c2r.place_experts(dev(Cm.astype(np.int32)), n_dev)
     assert np.array_equal(host(got), orc.place_experts(Cm, n_dev))
+
+
+@pytest.mark.parametrize("E,kind", [(8, "random"), (60, "profile"), (64, "random"), (16, "sparse"), (1, "random")])
+def test_collaboration_degree(c2r, orc, E, kind):
+    # Eq. 3 in fp64 on the device against the numpy definition; the bar is rounding order only
+    rng = np.random.default_rng(100 + E)
+    if kind == "profile":
+        w = wl.WORKLOADS["C3"]
+        Wg, b = wl.router(w)
+        idx, _ = orc.route(orc.logits_canon_f32(wl.hidden(w, 4096, stream=1), Wg, b), w.K)
+        Cm = orc.coactivation(idx, w.E)
+    else:
+        Cm = rng.integers(0, 1 << 20, size=(E, E))
+        Cm = Cm + Cm.T
+        if kind == "sparse":
+            Cm[rng.random((E, E)) < 0.6] = 0
+            Cm[3, :] = 0          # an expert that is never co-activated: degree 0
+            Cm[3, 3] = 77         # the diagonal takes no part
+    got = host(c2r.collaboration_degree(dev(Cm.astype(np.int32))))
+    ref = orc.collaboration_degree(Cm)
+    assert got.dtype == np.float64 and got.shape == (E,)
+    np.testing.assert_allclose(got, ref, rtol=1e-13, atol=1e-15)
+    if kind == "sparse":
+        assert got[3] == 0.0
+
+
+@pytest.mark.parametrize("T,K,E,eps", [(1000, 4, 60, (2, 3, 4, 5, 6)), (4097, 2, 8, (2, 4, 8)), (1, 4, 64, (64,)),
+                                       (70000, 4, 60, (1, 2, 3, 4, 5, 6, 10, 12)), (0, 4, 60, (2,))])
+def test_distinct_devices(c2r, orc, T, K, E, eps):
+    # per-token counts and totals for several expert-parallel degrees in one pass; exact
+    rng = np.random.default_rng(T + K + E)
+    idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32) if T else np.zeros((0, K), np.int32)
+    n_dev = max(eps)
+    maps = np.stack([rng.permutation(wl.device_map(E, ep) if E % ep == 0 else np.arange(E) % ep) for ep in eps])
+    tot, pt = c2r.distinct_devices(dev(idx), E, dev(maps.astype(np.int32)), n_dev, per_token=True)
+    tot, pt = host(tot), host(pt)
+    for m in range(len(eps)):
+        ref = orc.distinct_devices(idx, maps[m]) if T else np.zeros(0, np.int32)
+        assert np.array_equal(pt[m], ref), eps[m]
+        assert tot[m] == int(ref.sum())
+    if T:
+        # the totals are the copies the zero-redundancy send list holds for the same map
+        n_send = int(host(c2r.dedup_dispatch(dev(idx), E, dev(maps[0].astype(np.int32)), n_dev)[1])[-1])
+        assert n_send == tot[0]
+        # experts without a device and empty slots are skipped
+        idx2, map2 = idx.copy(), maps[0].astype(np.int32).copy()
+        idx2[::3, 0] = -1
+        map2[::5] = -1
+        ref = np.array([len({map2[e] for e in row if e >= 0 and map2[e] >= 0}) for row in idx2])
+        tot2, pt2 = c2r.distinct_devices(dev(idx2), E, dev(map2), n_dev, per_token=True)
+        assert np.array_equal(host(pt2)[0], ref) and int(host(tot2)[0]) == int(ref.sum())
