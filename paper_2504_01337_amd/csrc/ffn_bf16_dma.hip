@@ -30,17 +30,26 @@ namespace c2r {
 // it guards later LDS reads with vmcnt(0) whenever its alias bookkeeping loses track
 // (it does across this kernel's unrolled ring), which serialises the pipeline.  Hidden
 // from it, the only waits on copies are the ones this file states (wait_copies_but).
-__device__ __forceinline__ void copy16_to_lds(const unsigned char *gsrc, unsigned char *lds) {
+// The source is a wave-uniform base (scalar registers) plus a 32-bit byte offset per lane:
+// no 64-bit address arithmetic per copy, and half the address bits to send.
+__device__ __forceinline__ void copy16_to_lds(const unsigned char *base, uint32_t off, unsigned char *lds) {
 #if defined(__HIP_DEVICE_COMPILE__)
     const uint32_t lds_addr = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
     asm volatile(
-        "s_mov_b32 m0, %1\n\t"
+        "s_mov_b32 m0, %2\n\t"
         "s_nop 0\n\t"
-        "global_load_lds_dwordx4 %0, off"
+        "global_load_lds_dwordx4 %0, %1"
         :
-        : "v"(gsrc), "s"(lds_addr)
+        : "v"(off), "s"(base), "s"(lds_addr)
         : "memory", "m0");
 #endif
+}
+
+// A pointer the compiler may keep in scalar registers (the value is the same in every lane).
+__device__ __forceinline__ const unsigned char *uniform_ptr(const unsigned char *p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v), hi = __builtin_amdgcn_readfirstlane((uint32_t)(v >> 32));
+    return reinterpret_cast<const unsigned char *>(((uint64_t)hi << 32) | lo);
 }
 
 // Wait until at most N of this wave's copies are still in flight (they complete in order);
@@ -147,10 +156,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     // With `gather`, A is the un-permuted activation matrix and row p of the sorted order is
     // A[gather[p] / gather_div] (the dispatch gather folded into the copy addresses).
     const unsigned char *baseA =
-        reinterpret_cast<const unsigned char *>(gather ? A : A + (size_t)g.row_begin * lda);
-    const unsigned char *baseB0 = reinterpret_cast<const unsigned char *>(B0 + (size_t)g.expert * N * Kdim);
+        uniform_ptr(reinterpret_cast<const unsigned char *>(gather ? A : A + (size_t)g.row_begin * lda));
+    const unsigned char *baseB0 = uniform_ptr(reinterpret_cast<const unsigned char *>(B0 + (size_t)g.expert * N * Kdim));
     const unsigned char *baseB1 =
-        MODE == 0 ? reinterpret_cast<const unsigned char *>(B1 + (size_t)g.expert * N * Kdim) : baseB0;
+        MODE == 0 ? uniform_ptr(reinterpret_cast<const unsigned char *>(B1 + (size_t)g.expert * N * Kdim)) : baseB0;
     uint32_t offA[GA], offB[GB], rowB[GB];
     int rowA[GA];
 #pragma unroll
@@ -195,13 +204,16 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     // with the matrix pipe idle.
     // `inner`: kt is known not to be the last slice (no k tail to clamp).
     auto copy_piece = [&](int kt, unsigned char *stage, int p, bool inner = false) {
-        const uint32_t kb = (uint32_t)kt * ROWB;
+        const uint32_t kb = (uint32_t)kt * ROWB;  // the slice's byte offset goes into the scalar base
         if (p < GA) {
-            copy16_to_lds(baseA + offA[p] + kb, stage + (wave * GA + p) * 1024);
+            copy16_to_lds(baseA + kb, offA[p], stage + (wave * GA + p) * 1024);
+        } else if (inner) {
+            const int i = p - GA, rg = wave * GB + i;
+            copy16_to_lds(baseB + kb, offB[i], stage + A_BYTES + rg * 1024);
         } else {  // a B chunk past K is taken from chunk 0: it meets A's zero padding
             const int i = p - GA, rg = wave * GB + i;
-            const bool clampB = !inner && ktail && kt == nk - 1 && kt * BK + chunkc[rg & 1] * 8 >= Kdim;
-            copy16_to_lds(baseB + (clampB ? rowB[i] : offB[i] + kb), stage + A_BYTES + rg * 1024);
+            const bool clampB = ktail && kt == nk - 1 && kt * BK + chunkc[rg & 1] * 8 >= Kdim;
+            copy16_to_lds(baseB, clampB ? rowB[i] : offB[i] + kb, stage + A_BYTES + rg * 1024);
         }
     };
     constexpr int NPIECE = GA + GB;
@@ -269,10 +281,13 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #define C2R_MFMA_HALF(AS, BS, H, I, J0) \
     C2R_MFMA(AS, BS, H, I, (J0));         \
     C2R_MFMA(AS, BS, H, I, (J0) + 1)
-#define C2R_KSTEP(AS, BS, H, CKT, CST, P0, NCP)     \
+#define C2R_KSTEP(AS, BS, H, CKT, CST, P0, NCP, EARLY) \
     do {                                            \
         __builtin_amdgcn_sched_barrier(0);          \
         C2R_MFMA_HALF(AS, BS, H, 0, 0);             \
+        __builtin_amdgcn_sched_barrier(0);          \
+        EARLY;                                      \
+        __builtin_amdgcn_sched_barrier(0);          \
         C2R_COPY_IF(0, NCP, CKT, CST, P0)           \
         C2R_MFMA_HALF(AS, BS, H, 0, 2);             \
         C2R_COPY_IF(1, NCP, CKT, CST, P0)           \
@@ -316,13 +331,15 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         const int n1 = c1 ? C2R_CPB : 0, n1b = c1 ? C2R_CPC : 0, n1c = c1 ? C2R_CPD : 0;
         const int n2 = STEADY || kt + 2 < nk ? C2R_CPA : 0;
         if (active) {
-            read_a(cur, 0, 1, 1);
-            C2R_KSTEP(0, 0, 0, kt + 1, nxt, C2R_CPA, n1);
+            // (the first reads of a slice go out after its first two MFMAs: the compiler's wait
+            // at the top of the loop body covers every LDS read in flight, and there the only
+            // ones in flight should be those the first MFMAs need anyway)
+            C2R_KSTEP(0, 0, 0, kt + 1, nxt, C2R_CPA, n1, read_a(cur, 0, 1, 1));
             read_a(cur, 1, 0, 0);
             read_b(cur, 1, 1);
-            C2R_KSTEP(1, 0, 1, kt + 1, nxt, C2R_CPA + C2R_CPB, n1b);
+            C2R_KSTEP(1, 0, 1, kt + 1, nxt, C2R_CPA + C2R_CPB, n1b, (void)0);
             read_a(cur, 1, 1, 1);
-            C2R_KSTEP(0, 1, 0, kt + 1, nxt, C2R_CPA + C2R_CPB + C2R_CPC, n1c);
+            C2R_KSTEP(0, 1, 0, kt + 1, nxt, C2R_CPA + C2R_CPB + C2R_CPC, n1c, (void)0);
         } else if (c1) {
             if (C2R_CPA <= 1) copy_piece(kt + 1, nxt, 1);
             if (C2R_CPA <= 2) copy_piece(kt + 1, nxt, 2);
@@ -339,7 +356,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
                 read_a(nxt, 0, 0, 0);
                 read_b(nxt, 0, 0);
             }
-            C2R_KSTEP(1, 1, 1, kt + 2, cur, 0, n2);
+            C2R_KSTEP(1, 1, 1, kt + 2, cur, 0, n2, (void)0);
         } else if (n2) {
             copy_piece(kt + 2, cur, 0);
             if (C2R_CPA > 1) copy_piece(kt + 2, cur, 1);
@@ -358,15 +375,15 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         auto short_copy = [&](int kt) {
             unsigned char *stage = smem + (kt % L_NSTAGE) * L_STAGE_BYTES;
             const uint32_t kb = (uint32_t)kt * ROWB;
-            copy16_to_lds(baseA + offA[0] + kb, stage + (wave * L_GA + 0) * 1024);
-            copy16_to_lds(baseA + offA[1] + kb, stage + (wave * L_GA + 1) * 1024);
+            copy16_to_lds(baseA + kb, offA[0], stage + (wave * L_GA + 0) * 1024);
+            copy16_to_lds(baseA + kb, offA[1], stage + (wave * L_GA + 1) * 1024);
             const bool last = ktail && kt == nk - 1;
             const bool clamp0 = last && kt * BK + chunkc[0] * 8 >= Kdim, clamp1 = last && kt * BK + chunkc[1] * 8 >= Kdim;
             unsigned char *sb = stage + L_A_BYTES + wave * GB * 1024;  // wave * GB is even: groups alternate parity
-            copy16_to_lds(baseB + (clamp0 ? rowB[0] : offB[0] + kb), sb);
-            copy16_to_lds(baseB + (clamp1 ? rowB[1] : offB[1] + kb), sb + 1024);
-            copy16_to_lds(baseB + (clamp0 ? rowB[2] : offB[2] + kb), sb + 2048);
-            copy16_to_lds(baseB + (clamp1 ? rowB[3] : offB[3] + kb), sb + 3072);
+            copy16_to_lds(baseB, clamp0 ? rowB[0] : offB[0] + kb, sb);
+            copy16_to_lds(baseB, clamp1 ? rowB[1] : offB[1] + kb, sb + 1024);
+            copy16_to_lds(baseB, clamp0 ? rowB[2] : offB[2] + kb, sb + 2048);
+            copy16_to_lds(baseB, clamp1 ? rowB[3] : offB[3] + kb, sb + 3072);
         };
         const bool upper = rows > 64;  // fragments 2, 3 of the M range exist
         short_copy(0);
