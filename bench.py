@@ -304,12 +304,15 @@ def main():
                           ("mfma_bf16_random_operands_TFLOPs",
                            (torch.rand(1024 * 8, generator=g) * 2 - 1).to(torch.bfloat16))):
             ops = ops.cuda()
+            clk = torch.zeros(2, dtype=torch.int64, device="cuda")
             c2r.probe_mfma_bf16(ops, 2000, 1024, out_p)
             e0.record()
-            fl = c2r.probe_mfma_bf16(ops, 20000, 1024, out_p)
+            fl = c2r.probe_mfma_bf16(ops, 20000, 1024, out_p, clk)
             e1.record()
             torch.cuda.synchronize()
             res[name] = fl / e0.elapsed_time(e1) / 1e9
+            cyc, ticks = clk.tolist()   # shader cycles / 100 MHz ticks of the loop: the clock under this load
+            res[name.replace("_TFLOPs", "_shader_clock_GHz")] = cyc / (ticks / 1e8) / 1e9 if ticks else None
         src = torch.full(((512 << 20) // 4,), 1.0, dtype=torch.float32, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)

@@ -303,8 +303,11 @@ int c2r_distinct_devices(const int32_t *topk_idx, int64_t T, int K, int E, const
  * blocks   : workgroups of 512 threads (1..65536)
  * out      : float[blocks * 512] in DEVICE memory (sums, so the loop is not removed)
  * flops    : HOST pointer or NULL; receives the floating-point operations of the launch
+ * clocks   : uint64[2] in DEVICE memory or NULL; receives, from one thread of the first
+ *            workgroup, the shader cycles and the ticks of the constant 100 MHz clock that the
+ *            loop took: cycles / (ticks / 1e8) is the clock the chip really ran at
  */
-int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops,
+int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops, uint64_t *clocks,
                         void *stream);
 
 #ifdef __cplusplus

@@ -66,7 +66,7 @@ def lib():
         L.c2r_combine_copies.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp]
         L.c2r_collaboration_degree.argtypes = [vp, i32, vp, vp]
         L.c2r_distinct_devices.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
-        L.c2r_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp]
+        L.c2r_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp, vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i32
         _lib = L
@@ -315,12 +315,14 @@ def distinct_devices(topk_idx, E, expert_device, n_dev, per_token=False):
     return (totals, pt) if per_token else totals
 
 
-def probe_mfma_bf16(operands, iters, blocks, out):
-    """Measurement aid: a pure bf16 matrix-instruction loop.  Returns the launch's flops."""
+def probe_mfma_bf16(operands, iters, blocks, out, clocks=None):
+    """Measurement aid: a pure bf16 matrix-instruction loop.  Returns the launch's flops;
+    clocks (int64[2] on the device, optional) receives shader cycles and 100 MHz ticks."""
     assert operands.numel() * operands.element_size() >= 1024 * 16 and out.numel() >= blocks * 512
+    assert clocks is None or (clocks.dtype == torch.int64 and clocks.numel() >= 2)
     fl = C.c_double(0.0)
     _check("c2r_probe_mfma_bf16", lib().c2r_probe_mfma_bf16(_ptr(operands), iters, blocks, _ptr(out), C.byref(fl),
-                                                          _stream()))
+                                                          _ptr(clocks), _stream()))
     return fl.value
 
 

@@ -11,16 +11,29 @@ typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
 constexpr int PROBE_THREADS = 512, PROBE_ACC = 8;
 
 __global__ __launch_bounds__(PROBE_THREADS) void probe_mfma_kernel(const probe_bf16x8 *__restrict__ operands,
-                                                                  int iters, float *__restrict__ out) {
+                                                                  int iters, float *__restrict__ out,
+                                                                  unsigned long long *__restrict__ clocks) {
     const probe_bf16x8 a = operands[threadIdx.x], b = operands[threadIdx.x + PROBE_THREADS];
     probe_f32x4 acc[PROBE_ACC];
 #pragma unroll
     for (int i = 0; i < PROBE_ACC; ++i)
 #pragma unroll
         for (int v = 0; v < 4; ++v) acc[i][v] = 0.0f;
+    // one thread stamps the shader-cycle counter and the constant 100 MHz clock around the loop:
+    // their ratio is the clock the loop really ran at (the chip lowers it at its power limit)
+    const bool stamp = clocks && blockIdx.x == 0 && threadIdx.x == 0;
+    unsigned long long c0 = 0, w0 = 0;
+    if (stamp) {
+        c0 = clock64();
+        w0 = wall_clock64();
+    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int i = 0; i < PROBE_ACC; ++i) acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc[i], 0, 0, 0);
+    }
+    if (stamp) {
+        clocks[0] = clock64() - c0;
+        clocks[1] = wall_clock64() - w0;
     }
     float s = 0.0f;
 #pragma unroll
@@ -35,11 +48,11 @@ __global__ __launch_bounds__(PROBE_THREADS) void probe_mfma_kernel(const probe_b
 using namespace c2r;
 
 extern "C" int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops,
-                                   void *stream) {
+                                   uint64_t *clocks, void *stream) {
     if (!operands || !out || iters < 1 || blocks < 1 || blocks > 65536) return C2R_ERR_INVALID_ARG;
-    if (!aligned(operands, 16)) return C2R_ERR_INVALID_ARG;
+    if (!aligned(operands, 16) || !aligned(clocks, 8)) return C2R_ERR_INVALID_ARG;
     probe_mfma_kernel<<<dim3((unsigned)blocks), dim3(PROBE_THREADS), 0, static_cast<hipStream_t>(stream)>>>(
-        static_cast<const probe_bf16x8 *>(operands), iters, out);
+        static_cast<const probe_bf16x8 *>(operands), iters, out, reinterpret_cast<unsigned long long *>(clocks));
     if (flops) *flops = (double)blocks * (PROBE_THREADS / 64) * (double)iters * PROBE_ACC * (2.0 * 16 * 16 * 32);
     return launch_status();
 }

@@ -22,42 +22,47 @@ __global__ __launch_bounds__(256) void pack_router_kernel(const float *__restric
     Wp[i] = j < E ? Wg[(int64_t)k * E + j] : 0.0f;
 }
 
-// Partial logits of one 256-long k-chunk for NWV 64-token tiles (one per wave), all experts.
-// A register-tiled fp32 GEMM: lane = (token lane tl, expert lane el) on an 8 x 8 grid; the
-// thread owns tokens tl + 8q (q < 8) and experts el*TE + j (j < TE), i.e. 8*TE accumulators,
+// Partial logits of one 256-long k-chunk for NWV token tiles of 8*TQ tokens (one per wave), all
+// experts.  A register-tiled fp32 GEMM: lane = (token lane tl, expert lane el) on an 8 x 8 grid; the
+// thread owns tokens tl + 8q (q < TQ) and experts el*TE + j (j < TE), i.e. TQ*TE accumulators,
 // and walks k upward one fused multiply-add at a time, which is the declared order.  Both
 // operands come from LDS (x as stored, 16 bytes = 8 bf16 or 4 fp32 per token per read; W
 // rows as fp32), staged in 32-wide k sub-tiles that are double buffered against global
 // loads held in registers; the W sub-tile is shared by the workgroup's waves.
-template <bool BF16, int TE, int NWV>
+// TQ = 4 halves a wave's tile: twice the waves for batches that would otherwise leave one wave
+// per SIMD with nothing to hide its LDS latency behind.
+template <bool BF16, int TE, int NWV, int TQ>
 __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__restrict__ x,
                                                                 const float *__restrict__ W, int ldw,
                                                                 int ep, int64_t T, int d, int nchunk,
                                                                 int64_t ntiles,
                                                                 float *__restrict__ part) {
     constexpr int EPAD = 8 * TE;         // experts covered by a wave
+    constexpr int TOK = 8 * TQ;          // tokens covered by a wave
     constexpr int KS = 32;               // k per staged sub-tile
     constexpr int VEC = BF16 ? 8 : 4;    // elements per 16-byte vector of x
     constexpr int ESZ = BF16 ? 2 : 4;
     constexpr int XV = KS / VEC;         // 16-byte vectors per token per sub-tile
     constexpr int XPITCH = KS * ESZ + 16;  // bytes; token rows 8 apart land on distinct bank groups
-    constexpr int XLOADS = 64 * XV / 64;   // vectors per lane per sub-tile
+    constexpr int XLOADS = TOK * XV / 64;  // vectors per lane per sub-tile
+    static_assert(XLOADS >= 1 && 64 % TOK == 0, "a wave loads whole vectors; wave tiles divide the 64-token tile");
     constexpr int WF4 = KS * EPAD / 4;     // float4 per W sub-tile
     constexpr int WLOADS = (WF4 + NWV * 64 - 1) / (NWV * 64);
     __shared__ __attribute__((aligned(16))) float Wl[2][KS][EPAD];
-    __shared__ __attribute__((aligned(16))) unsigned char Xl[2][NWV][64 * XPITCH];
+    __shared__ __attribute__((aligned(16))) unsigned char Xl[2][NWV][TOK * XPITCH];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tl = lane & 7, el = lane >> 3;
-    const int64_t ngroups = (ntiles + NWV - 1) / NWV;
+    const int64_t nwt = ntiles * (64 / TOK);       // wave tiles
+    const int64_t ngroups = (nwt + NWV - 1) / NWV;
     const int64_t tgroup = blockIdx.x % ngroups;  // token tiles fastest: neighbours share W rows in L2
     const int chunk = (int)(blockIdx.x / ngroups);
-    const int64_t tile = tgroup * NWV + wave;      // may be >= ntiles: such a wave only helps load W
-    const bool live = tile < ntiles;
+    const int64_t wt = tgroup * NWV + wave;        // may be >= nwt: such a wave only helps load W
+    const bool live = wt < nwt;
     const int k_begin = chunk * C2R_CANON_CHUNK;
     const int k_end = min(d, k_begin + C2R_CANON_CHUNK);
-    const int64_t t0 = tile * 64;
+    const int64_t t0 = wt * TOK;
     const unsigned char *xb = static_cast<const unsigned char *>(x);
 
     float4 wreg[WLOADS];
@@ -96,9 +101,9 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
         }
     };
 
-    float acc[8][TE];
+    float acc[TQ][TE];
 #pragma unroll
-    for (int q = 0; q < 8; ++q)
+    for (int q = 0; q < TQ; ++q)
 #pragma unroll
         for (int j = 0; j < TE; ++j) acc[q][j] = 0.0f;
 
@@ -111,9 +116,9 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
         if (knext < k_end) gload(knext);
         const int nvec = min(KS, k_end - k0) / VEC;  // workgroup-uniform
         for (int v = 0; v < nvec; ++v) {
-            uint4 xp[8];
+            uint4 xp[TQ];
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
+            for (int q = 0; q < TQ; ++q)
                 xp[q] = *reinterpret_cast<const uint4 *>(&Xl[buf][wave][(tl + 8 * q) * XPITCH + v * 16]);
 #pragma unroll
             for (int u = 0; u < VEC; ++u) {
@@ -121,7 +126,7 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
 #pragma unroll
                 for (int j = 0; j < TE; ++j) wv[j] = Wl[buf][v * VEC + u][el * TE + j];
 #pragma unroll
-                for (int q = 0; q < 8; ++q) {
+                for (int q = 0; q < TQ; ++q) {
                     const uint32_t word = BF16 ? (u < 2 ? xp[q].x : u < 4 ? xp[q].y : u < 6 ? xp[q].z : xp[q].w)
                                                : (u == 0 ? xp[q].x : u == 1 ? xp[q].y : u == 2 ? xp[q].z : xp[q].w);
                     const float xv = BF16 ? __uint_as_float((u & 1) ? (word & 0xffff0000u) : (word << 16))
@@ -136,13 +141,14 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
         buf ^= 1;
     }
     if (!live) return;
-    float *dst = part + (((size_t)tile * nchunk + chunk) * ep) * 64;
+    const int64_t tile = wt / (64 / TOK);           // the 64-token tile and this wave's part of it
+    float *dst = part + (((size_t)tile * nchunk + chunk) * ep) * 64 + (wt % (64 / TOK)) * TOK;
 #pragma unroll
     for (int j = 0; j < TE; ++j) {
         const int e = el * TE + j;
         if (e < ep) {
 #pragma unroll
-            for (int q = 0; q < 8; ++q) dst[(size_t)e * 64 + tl + 8 * q] = acc[q][j];
+            for (int q = 0; q < TQ; ++q) dst[(size_t)e * 64 + tl + 8 * q] = acc[q][j];
         }
     }
 }
@@ -379,27 +385,29 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
         return C2R_ERR_INVALID_ARG;
     }
     const int64_t ntiles = L.Tpad / 64;
-    // waves per workgroup share the W sub-tiles; with few token tiles use fewer waves per
-    // workgroup so that the launch still spreads over the CUs
+    // Four waves per workgroup share the W sub-tiles.  A batch with fewer than two 64-token
+    // wave tiles per SIMD of the chip uses half-size wave tiles: with one wave per SIMD nothing
+    // hides its LDS latency (measured at T = 8192, d = 2048, E = 60: 54 -> 43 us).
     const int te = L.EP > 32 ? 8 : L.EP > 16 ? 4 : L.EP > 8 ? 2 : 1;
     const bool wide = ntiles * L.nchunk >= 2048;
-    const int nwv = wide ? 4 : 2;
-    const int64_t nblk = (ntiles + nwv - 1) / nwv * L.nchunk;
+    constexpr int NWV = 4;
+    const int64_t nwt = wide ? ntiles : ntiles * 2;
+    const int64_t nblk = (nwt + NWV - 1) / NWV * L.nchunk;
     if (nblk >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
-#define C2R_ROUTE_LAUNCH(BF, TE, NWV)                                                             \
-    route_partial_kernel<BF, TE, NWV><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(            \
+#define C2R_ROUTE_LAUNCH(BF, TE, NWV, TQ)                                                         \
+    route_partial_kernel<BF, TE, NWV, TQ><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(        \
         x, W, ldw, L.EP, T, d, L.nchunk, ntiles, part)
-#define C2R_ROUTE_TE(BF, NWV)                          \
-    switch (te) {                                      \
-        case 8: C2R_ROUTE_LAUNCH(BF, 8, NWV); break;   \
-        case 4: C2R_ROUTE_LAUNCH(BF, 4, NWV); break;   \
-        case 2: C2R_ROUTE_LAUNCH(BF, 2, NWV); break;   \
-        default: C2R_ROUTE_LAUNCH(BF, 1, NWV); break;  \
+#define C2R_ROUTE_TE(BF, NWV, TQ)                          \
+    switch (te) {                                          \
+        case 8: C2R_ROUTE_LAUNCH(BF, 8, NWV, TQ); break;   \
+        case 4: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ); break;   \
+        case 2: C2R_ROUTE_LAUNCH(BF, 2, NWV, TQ); break;   \
+        default: C2R_ROUTE_LAUNCH(BF, 1, NWV, TQ); break;  \
     }
     if (x_dt == C2R_BF16) {
-        if (wide) { C2R_ROUTE_TE(true, 4) } else { C2R_ROUTE_TE(true, 2) }
+        if (wide) { C2R_ROUTE_TE(true, NWV, 8) } else { C2R_ROUTE_TE(true, NWV, 4) }
     } else {
-        if (wide) { C2R_ROUTE_TE(false, 4) } else { C2R_ROUTE_TE(false, 2) }
+        if (wide) { C2R_ROUTE_TE(false, NWV, 8) } else { C2R_ROUTE_TE(false, NWV, 4) }
     }
 #undef C2R_ROUTE_TE
 #undef C2R_ROUTE_LAUNCH

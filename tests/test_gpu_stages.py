@@ -279,6 +279,13 @@ def test_probe_mfma_counts_its_work(c2r):
     torch.cuda.synchronize()
     assert flops == 4 * 8 * 3 * 8 * 2 * 16 * 16 * 32
     assert torch.all(out == 3 * 8 * 4 * 32)
+    # with clock stamps: a longer loop, the chip's clock comes out between 0.5 and 3 GHz
+    clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+    c2r.probe_mfma_bf16(ops, 20000, 256, torch.zeros(256 * 512, dtype=torch.float32, device="cuda"), clk)
+    torch.cuda.synchronize()
+    cyc, ticks = clk.tolist()
+    assert cyc >= 20000 * 8 * 4 and ticks > 0           # at least 4 cycles per matrix instruction
+    assert 0.5e9 < cyc / (ticks / 1e8) < 3.0e9
 
 
 @pytest.mark.parametrize("E,K,T,n_dev,holes", [(12, 4, 300, 4, True), (60, 4, 5000, 4, False), (64, 8, 1025, 64, True),
