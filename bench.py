@@ -98,9 +98,11 @@ def main():
     stages = [s for s in L.STAGES if shared or not s.startswith("shared")]
     dom_stages = [s for s in ("ffn_gate_up", "shared_gate_up") if s in stages]   # launches of the dominant kernel
     mk = lambda: torch.cuda.Event(enable_timing=True)
-    # timed region: only the dominant kernel's launches carry events (an event record costs a
-    # few microseconds of stream time; fourteen of them per step were 3 % of the step)
-    ev_dom = [{s: (mk(), mk()) for s in dom_stages} for _ in range(args.steps)]
+    # timed region: only the dominant kernel's launches carry events, and only on every fourth
+    # step (an event record holds the stream for 5.6 us: fourteen per step were 3 % of the step,
+    # the four around the two gate/up launches still 1.9 %)
+    ev_every = 4 if args.steps >= 8 else 1
+    ev_dom = [{s: (mk(), mk()) for s in dom_stages} if i % ev_every == 0 else None for i in range(args.steps)]
     ev = [{s: (mk(), mk()) for s in stages} for _ in range(args.steps)]
 
     for _ in range(args.warmup):
@@ -113,8 +115,9 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = w.T / (ms_per_step * 1e-3)
-    dom_ms_live = {s: float(np.mean([ev_dom[i][s][0].elapsed_time(ev_dom[i][s][1]) for i in range(args.steps)]))
+    dom_ms_live = {s: float(np.mean([e[s][0].elapsed_time(e[s][1]) for e in ev_dom if e is not None]))
                    for s in dom_stages}
+    dom_launches_timed = sum(len(dom_stages) for e in ev_dom if e is not None)
 
     # stage breakdown: the same steps again, every stage bracketed by events (not part of `value`)
     for i in range(args.steps):
@@ -287,12 +290,12 @@ def main():
         roofline = {"kernel": "ffn_bf16_dma_kernel<0>" + both + " (gate/up + SwiGLU)", "bound": "mfma",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["mfma_bf16_TFLOPs"], "unit": "TFLOP/s",
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["mfma_bf16_TFLOPs"], "traffic": traffic,
-                    "avg_launch_ms": dom_ms, "launches_per_step": n_launch}
+                    "avg_launch_ms": dom_ms, "launches_per_step": n_launch, "launches_timed": dom_launches_timed}
     else:
         roofline = {"kernel": "ffn_f32_kernel<0>" + both + " (gate/up + SwiGLU)", "bound": "alu",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["valu_f32_TFLOPs"], "unit": "TFLOP/s",
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["valu_f32_TFLOPs"], "traffic": None,
-                    "avg_launch_ms": dom_ms, "launches_per_step": n_launch}
+                    "avg_launch_ms": dom_ms, "launches_per_step": n_launch, "launches_timed": dom_launches_timed}
 
     # ---- measured ceilings of this machine: matrix pipe (zeros / random operands) and a device copy ----
     def measured_ceilings():

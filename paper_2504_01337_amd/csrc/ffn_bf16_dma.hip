@@ -255,6 +255,13 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #pragma unroll
         for (int i = 0; i < 4; ++i) aset[set][i] = *reinterpret_cast<const bf16x8 *>(stage + rdA[half * 4 + i] + ch);
     };
+    // the first n (wave-uniform, 1..4) of them only
+    auto read_a_first = [&](const unsigned char *stage, int kq, int half, int set, int n) {
+        const uint32_t ch = (uint32_t)(((kq * 4 + fq) ^ sw) * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (i < n) aset[set][i] = *reinterpret_cast<const bf16x8 *>(stage + rdA[half * 4 + i] + ch);
+    };
     auto read_b = [&](const unsigned char *stage, int kq, int set) {
         const uint32_t ch = (uint32_t)(((kq * 4 + fq) ^ sw) * 16);
 #pragma unroll
@@ -385,7 +392,10 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             copy16_to_lds(baseB, clamp0 ? rowB[2] : offB[2] + kb, sb + 2048);
             copy16_to_lds(baseB, clamp1 ? rowB[3] : offB[3] + kb, sb + 3072);
         };
-        const bool upper = rows > 64;  // fragments 2, 3 of the M range exist
+        // Only the 16-row fragments that hold rows of the group are computed: most short tiles
+        // belong to experts with a handful of tokens, the chip is power limited, and matrix
+        // instructions on padding rows cost the other workgroups clock.
+        const int nf = (rows + 15) >> 4;  // 1..8, workgroup-uniform
         short_copy(0);
         if (nk > 1) short_copy(1);
         for (int kt = 0; kt < nk; ++kt) {
@@ -402,17 +412,17 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #pragma unroll
                 for (int kq = 0; kq < 2; ++kq) {
                     read_b(stage, kq, 0);
-                    read_a(stage, kq, 0, 0);
+                    read_a_first(stage, kq, 0, 0, nf);
                     C2R_MFMA_ROW(0, 0, 0, 0);
-                    C2R_MFMA_ROW(0, 0, 0, 1);
-                    C2R_MFMA_ROW(0, 0, 0, 2);
-                    C2R_MFMA_ROW(0, 0, 0, 3);
-                    if (upper) {
-                        read_a(stage, kq, 1, 1);
+                    if (nf > 1) { C2R_MFMA_ROW(0, 0, 0, 1); }
+                    if (nf > 2) { C2R_MFMA_ROW(0, 0, 0, 2); }
+                    if (nf > 3) { C2R_MFMA_ROW(0, 0, 0, 3); }
+                    if (nf > 4) {
+                        read_a_first(stage, kq, 1, 1, nf - 4);
                         C2R_MFMA_ROW(1, 0, 1, 0);
-                        C2R_MFMA_ROW(1, 0, 1, 1);
-                        C2R_MFMA_ROW(1, 0, 1, 2);
-                        C2R_MFMA_ROW(1, 0, 1, 3);
+                        if (nf > 5) { C2R_MFMA_ROW(1, 0, 1, 1); }
+                        if (nf > 6) { C2R_MFMA_ROW(1, 0, 1, 2); }
+                        if (nf > 7) { C2R_MFMA_ROW(1, 0, 1, 3); }
                     }
                 }
             }

@@ -3,8 +3,7 @@
 //
 //  1. permute_hist_kernel   per-block LDS histogram of local slots
 //  2. permute_scan_kernel   counts, exclusive offsets, and the start position of
-//                           every (block, slot) run (folded into step 3 when there are
-//                           few blocks: each block sums the histograms it needs itself)
+//                           every (block, slot) run
 //  3. permute_rank_kernel   stable rank inside the block: each wave step ranks
 //                           its 64 assignments with ballots (equal keys keep
 //                           lane order), an LDS prefix over the block's wave
@@ -12,6 +11,7 @@
 //  4. permute_rows_kernel   one wave per token: the row of x is read once and
 //                           written to each of its (up to K) sorted positions
 //                           with 16-byte accesses
+// Up to 2^18 assignments, steps 1-3 are one launch instead (permute_by_slot_kernel).
 // Everything is deterministic: no atomically assigned slots.
 #include "c2r_internal.h"
 
@@ -78,51 +78,11 @@ __global__ __launch_bounds__(64) void permute_scan_kernel(const int32_t *__restr
     }
 }
 
-// FUSED: there are few blocks, so every block derives the run starts itself from the block
-// histograms (and block 0 also writes counts / offsets) instead of a separate scan launch.
-template <bool FUSED>
 __global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(
     const int32_t *__restrict__ topk_idx, int64_t A, int E, const int32_t *__restrict__ local_slot,
-    int E_local, const int32_t *__restrict__ block_base, const int32_t *__restrict__ block_counts,
-    int nblocks, int32_t *__restrict__ counts, int32_t *__restrict__ offsets,
-    int32_t *__restrict__ perm, int32_t *__restrict__ inv_perm) {
+    int E_local, const int32_t *__restrict__ block_base, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv_perm) {
     __shared__ int32_t step_cnt[PB_STEPS][C2R_MAX_E];
-    __shared__ int32_t part_tot[PB_THREADS / 64][C2R_MAX_E], part_pre[PB_THREADS / 64][C2R_MAX_E];
-    __shared__ int32_t run_base[C2R_MAX_E];
-    if (FUSED) {
-        const int e = threadIdx.x & 63, part = threadIdx.x >> 6;
-        int32_t tot = 0, pre = 0;
-        if (e < E_local) {
-            for (int b = part; b < nblocks; b += PB_THREADS / 64) {
-                const int32_t v = block_counts[(size_t)b * E_local + e];
-                tot += v;
-                if (b < (int)blockIdx.x) pre += v;
-            }
-        }
-        part_tot[part][e] = tot;
-        part_pre[part][e] = pre;
-        __syncthreads();
-        if (threadIdx.x < 64) {
-            int32_t total = 0, before = 0;
-#pragma unroll
-            for (int q = 0; q < PB_THREADS / 64; ++q) {
-                total += part_tot[q][e];
-                before += part_pre[q][e];
-            }
-            int32_t incl = total;
-#pragma unroll
-            for (int off = 1; off < 64; off <<= 1) {
-                const int32_t v = __shfl_up(incl, off);
-                if (e >= off) incl += v;
-            }
-            run_base[e] = incl - total + before;
-            if (blockIdx.x == 0 && e < E_local) {
-                counts[e] = total;
-                offsets[e] = incl - total;
-                if (e == E_local - 1) offsets[E_local] = incl;
-            }
-        }
-    }
     for (int i = threadIdx.x; i < PB_STEPS * C2R_MAX_E; i += PB_THREADS) (&step_cnt[0][0])[i] = 0;
     __syncthreads();
 
@@ -153,7 +113,7 @@ __global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(
     __syncthreads();
     // exclusive prefix over the block's wave steps, per slot, seeded with the block's start
     if (threadIdx.x < E_local) {
-        int32_t run = FUSED ? run_base[threadIdx.x] : block_base[(size_t)blockIdx.x * E_local + threadIdx.x];
+        int32_t run = block_base[(size_t)blockIdx.x * E_local + threadIdx.x];
 #pragma unroll
         for (int q = 0; q < PB_STEPS; ++q) {
             const int32_t c = step_cnt[q][threadIdx.x];
@@ -174,6 +134,105 @@ __global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(
             } else {
                 inv_perm[a] = -1;
             }
+        }
+    }
+}
+
+// Small batches (the whole index array is a few hundred KB and sits in L2): one launch, one
+// workgroup per local expert slot.  The workgroup's 16 waves each own a contiguous
+// sixteenth of the assignments; a first sweep counts, per wave, the assignments of this
+// slot and of all lower slots, a second sweep hands out the positions in order (ballot +
+// prefix inside a 64-assignment step, running count across steps, wave totals across
+// waves), which is the same stable order as the counting sort above.  Workgroup 0 also
+// marks the assignments that belong to no local slot.
+constexpr int PE_WAVES = 16;
+constexpr int PE_STEPS = 32;  // 64-assignment steps a wave holds in registers at a time
+
+__global__ __launch_bounds__(PE_WAVES * 64) void permute_by_slot_kernel(
+    const int32_t *__restrict__ topk_idx, int A, int E, const int32_t *__restrict__ local_slot, int E_local,
+    int32_t *__restrict__ counts, int32_t *__restrict__ offsets, int32_t *__restrict__ perm,
+    int32_t *__restrict__ inv_perm) {
+    __shared__ int32_t w_mine[PE_WAVES], w_less[PE_WAVES];
+    const int e = blockIdx.x, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int seg = ((A + PE_WAVES - 1) / PE_WAVES + 63) / 64 * 64;  // assignments per wave, whole steps
+    const int a_begin = wave * seg, a_end = min(A, a_begin + seg);
+    // Up to 2048 assignments per wave (A <= 32768) the slots are loaded once, all loads in
+    // flight together, and stay in registers for both sweeps; longer segments go in pieces
+    // of that size and are read again by the second sweep.
+    const bool single = seg <= PE_STEPS * 64;
+    int sl[PE_STEPS];
+    // (every load is unconditional, on a clamped index, so that all of them are in flight at
+    // once: guarded loads end up one branch and one memory round trip each)
+    auto load = [&](int c0) {
+#pragma unroll
+        for (int u = 0; u < PE_STEPS; ++u) sl[u] = topk_idx[min(c0 + u * 64 + lane, A - 1)];
+        if (local_slot) {
+            int ex[PE_STEPS];
+#pragma unroll
+            for (int u = 0; u < PE_STEPS; ++u) ex[u] = sl[u];
+#pragma unroll
+            for (int u = 0; u < PE_STEPS; ++u) sl[u] = local_slot[min(max(ex[u], 0), E - 1)];
+#pragma unroll
+            for (int u = 0; u < PE_STEPS; ++u) sl[u] = (ex[u] >= 0 && ex[u] < E) ? sl[u] : -1;
+        } else {
+#pragma unroll
+            for (int u = 0; u < PE_STEPS; ++u) sl[u] = sl[u] < E ? sl[u] : -1;
+        }
+#pragma unroll
+        for (int u = 0; u < PE_STEPS; ++u) {
+            const bool slot_ok = sl[u] >= 0 && sl[u] < E_local;
+            sl[u] = c0 + u * 64 + lane < a_end ? (slot_ok ? sl[u] : -1) : -2;  // -2: past the end
+        }
+    };
+    int mine = 0, less = 0;
+    for (int c0 = a_begin; c0 < a_end; c0 += PE_STEPS * 64) {
+        load(c0);
+#pragma unroll
+        for (int u = 0; u < PE_STEPS; ++u) {
+            mine += sl[u] == e;
+            less += sl[u] >= 0 && sl[u] < e;
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        mine += __shfl_xor(mine, off);
+        less += __shfl_xor(less, off);
+    }
+    if (lane == 0) {
+        w_mine[wave] = mine;
+        w_less[wave] = less;
+    }
+    __syncthreads();
+    int start = 0, total = 0;  // this slot's first position; its count
+#pragma unroll
+    for (int w = 0; w < PE_WAVES; ++w) {
+        start += w_less[w];
+        total += w_mine[w];
+    }
+    int run = start;
+#pragma unroll
+    for (int w = 0; w < PE_WAVES; ++w) run += w < wave ? w_mine[w] : 0;
+    if (threadIdx.x == 0) {
+        counts[e] = total;
+        offsets[e] = start;
+        if (e == E_local - 1) offsets[E_local] = start + total;
+    }
+    const uint64_t lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    for (int c0 = a_begin; c0 < a_end; c0 += PE_STEPS * 64) {
+        if (!single) load(c0);
+#pragma unroll
+        for (int u = 0; u < PE_STEPS; ++u) {
+            const int a = c0 + u * 64 + lane;
+            const uint64_t m = __ballot(sl[u] == e);
+            if (sl[u] == e) {
+                const int p = run + __popcll(m & lt);
+                perm[p] = a;
+                inv_perm[a] = p;
+            } else if (e == 0 && sl[u] == -1) {
+                inv_perm[a] = -1;
+            }
+            run += __popcll(m);
         }
     }
 }
@@ -244,22 +303,21 @@ extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx,
     if (nblocks > 0 && (!ws || ws_bytes < 2 * half || !aligned(ws, 256))) return C2R_ERR_WORKSPACE;
     int32_t *block_counts = static_cast<int32_t *>(ws);
     int32_t *block_base = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + half);
-    if (nblocks > 0)
-        permute_hist_kernel<<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
-            topk_idx, A, E, local_slot, E_local, block_counts);
-    const bool fused = nblocks > 0 && nblocks <= 256;  // each block re-reads nblocks*E_local counts
-    if (!fused)
-        permute_scan_kernel<<<dim3(1), dim3(64), 0, st>>>(block_counts, (int)nblocks, E_local, block_base,
-                                                          counts, offsets);
+    if (A > 0 && A <= (1 << 18)) {
+        // the index array is swept once per slot out of L2, in one launch
+        permute_by_slot_kernel<<<dim3((unsigned)E_local), dim3(PE_WAVES * 64), 0, st>>>(
+            topk_idx, (int)A, E, local_slot, E_local, counts, offsets, perm, inv_perm);
+    } else {
+        if (nblocks > 0)
+            permute_hist_kernel<<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
+                topk_idx, A, E, local_slot, E_local, block_counts);
+        permute_scan_kernel<<<dim3(1), dim3(64), 0, st>>>(block_counts, (int)nblocks, E_local, block_base, counts,
+                                                          offsets);
+        if (nblocks > 0)
+            permute_rank_kernel<<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
+                topk_idx, A, E, local_slot, E_local, block_base, perm, inv_perm);
+    }
     if (nblocks > 0) {
-        if (fused)
-            permute_rank_kernel<true><<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
-                topk_idx, A, E, local_slot, E_local, block_base, block_counts, (int)nblocks, counts, offsets,
-                perm, inv_perm);
-        else
-            permute_rank_kernel<false><<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
-                topk_idx, A, E, local_slot, E_local, block_base, block_counts, (int)nblocks, counts, offsets,
-                perm, inv_perm);
         if (x_perm) {
             const int row_vecs = d * (dt == C2R_BF16 ? 2 : 4) / 16;
             permute_rows_kernel<<<dim3((unsigned)((T + 3) / 4)), dim3(256), 0, st>>>(
