@@ -310,6 +310,27 @@ int c2r_distinct_devices(const int32_t *topk_idx, int64_t T, int K, int E, const
 int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops, uint64_t *clocks,
                         void *stream);
 
+/*
+ * Measurement aid, not a step of the path: the duration of ONE launch of the fast bf16
+ * expert-FFN kernel (bf16, d a multiple of 64), taken from the dispatch's own start and end
+ * time stamps.  Stream markers around a launch hold the stream for several microseconds each
+ * and would be inside the benchmark's timed region; this costs the stream nothing.
+ *   create   : makes a timer (a HOST object holding two events; the one exception to "the
+ *              library allocates nothing": no device memory is involved)
+ *   arm      : the next such launch enqueued by THIS host thread (by c2r_expert_ffn,
+ *              _gate_up, _gate_up_gather or _down; for c2r_expert_ffn the first of its two
+ *              passes) records into the timer; arming again before a launch replaces the
+ *              previous arming.  Launches of the other FFN kernels (fp32, generic bf16) do not
+ *              take a timer.
+ *   elapsed  : waits for that launch to finish and returns its duration in milliseconds;
+ *              C2R_ERR_INVALID_ARG if no launch has taken the timer since it was armed
+ *   destroy  : frees the timer (disarming it if armed)
+ */
+int c2r_launch_timer_create(void **timer);
+int c2r_launch_timer_arm(void *timer);
+int c2r_launch_timer_elapsed_ms(void *timer, float *ms);
+int c2r_launch_timer_destroy(void *timer);
+
 #ifdef __cplusplus
 }
 #endif

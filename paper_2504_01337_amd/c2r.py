@@ -25,7 +25,8 @@ EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_c
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine",
            "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies",
-           "c2r_collaboration_degree", "c2r_distinct_devices", "c2r_probe_mfma_bf16"]
+           "c2r_collaboration_degree", "c2r_distinct_devices", "c2r_probe_mfma_bf16",
+           "c2r_launch_timer_create", "c2r_launch_timer_arm", "c2r_launch_timer_elapsed_ms", "c2r_launch_timer_destroy"]
 
 
 class C2RError(RuntimeError):
@@ -67,6 +68,10 @@ def lib():
         L.c2r_collaboration_degree.argtypes = [vp, i32, vp, vp]
         L.c2r_distinct_devices.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
         L.c2r_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp, vp]
+        L.c2r_launch_timer_create.argtypes = [C.POINTER(vp)]
+        L.c2r_launch_timer_arm.argtypes = [vp]
+        L.c2r_launch_timer_elapsed_ms.argtypes = [vp, C.POINTER(C.c_float)]
+        L.c2r_launch_timer_destroy.argtypes = [vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i32
         _lib = L
@@ -326,6 +331,29 @@ def probe_mfma_bf16(operands, iters, blocks, out, clocks=None):
     return fl.value
 
 
+class LaunchTimer:
+    """Measurement aid: the duration of one launch of the fast bf16 expert-FFN kernel, from the
+    dispatch's own time stamps.  arm() before the call that launches it, elapsed_ms() after."""
+
+    def __init__(self):
+        h = C.c_void_p()
+        _check("c2r_launch_timer_create", lib().c2r_launch_timer_create(C.byref(h)))
+        self._h = h
+
+    def arm(self):
+        _check("c2r_launch_timer_arm", lib().c2r_launch_timer_arm(self._h))
+
+    def elapsed_ms(self) -> float:
+        ms = C.c_float()
+        _check("c2r_launch_timer_elapsed_ms", lib().c2r_launch_timer_elapsed_ms(self._h, C.byref(ms)))
+        return ms.value
+
+    def __del__(self):
+        if getattr(self, "_h", None) is not None and _lib is not None:
+            _lib.c2r_launch_timer_destroy(self._h)
+            self._h = None
+
+
 class C2RLayer:
     """One C2R MoE layer with all buffers allocated up front: forward() only
     enqueues the library's stages (no allocation, no host synchronisation).
@@ -388,11 +416,12 @@ class C2RLayer:
     # names of the stages forward() runs, in the order a trace lists them
     STAGES = ("route", "permute", "ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down", "combine")
 
-    def forward(self, x, trace=None, only=None):
+    def forward(self, x, trace=None, only=None, timers=None):
         """y = layer(x).  trace: optional {stage: (start_event, end_event)} for any subset of
         STAGES; each pair is recorded on the stream its stage runs on (timing events, made by
         the caller).  only: run just that stage on the buffers a previous full call left
-        (for timing a stage on its own)."""
+        (for timing a stage on its own).  timers: optional {stage: LaunchTimer}, armed before
+        the stage's call (stages that launch the fast bf16 FFN kernel)."""
         main = torch.cuda.current_stream()
         side = self.side if self.overlap else main
 
@@ -403,6 +432,8 @@ class C2RLayer:
             with torch.cuda.stream(stream):
                 if pair is not None:
                     pair[0].record(stream)
+                if timers is not None and name in timers:
+                    timers[name].arm()
                 fn()
                 if pair is not None:
                     pair[1].record(stream)

@@ -34,6 +34,14 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xffffu; }
 
+// Measurement aid (c2r_launch_timer_*): a pair of events that the next launch of the fast bf16
+// expert-FFN kernel on this host thread attaches to its dispatch.
+struct LaunchTimer {
+    hipEvent_t start, stop;
+    bool fired;
+};
+extern thread_local LaunchTimer *armed_launch_timer;
+
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (C2R_WAVE - 1); }
 
 }  // namespace c2r

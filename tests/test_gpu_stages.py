@@ -413,3 +413,28 @@ def test_distinct_devices(c2r, orc, T, K, E, eps):
         ref = np.array([len({map2[e] for e in row if e >= 0 and map2[e] >= 0}) for row in idx2])
         tot2, pt2 = c2r.distinct_devices(dev(idx2), E, dev(map2), n_dev, per_token=True)
         assert np.array_equal(host(pt2)[0], ref) and int(host(tot2)[0]) == int(ref.sum())
+
+
+def test_launch_timer(c2r):
+    # the timer takes the next launch of the fast bf16 FFN kernel on this thread, and only that one
+    T, d, F = 512, 256, 128
+    x = torch.randn(T, d, device="cuda").to(torch.bfloat16)
+    wg = torch.randn(1, F, d, device="cuda").to(torch.bfloat16)
+    wu = torch.randn(1, F, d, device="cuda").to(torch.bfloat16)
+    off = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+    h_plain = torch.empty(T, F, dtype=torch.bfloat16, device="cuda")
+    h_timed = torch.empty_like(h_plain)
+    c2r.expert_ffn_gate_up(x, off, wg, wu, h_plain)
+    tm = c2r.LaunchTimer()
+    with pytest.raises(c2r.C2RError):
+        tm.elapsed_ms()                      # never armed
+    tm.arm()
+    with pytest.raises(c2r.C2RError):
+        tm.elapsed_ms()                      # armed, nothing launched yet
+    c2r.expert_ffn_gate_up(x, off, wg, wu, h_timed)
+    ms = tm.elapsed_ms()
+    assert 0.0 < ms < 50.0
+    assert torch.equal(h_plain, h_timed)     # same kernel, same result
+    c2r.expert_ffn_gate_up(x, off, wg, wu, h_timed)     # not armed: an ordinary launch
+    torch.cuda.synchronize()
+    assert tm.elapsed_ms() == ms             # the timer still holds the launch it took
