@@ -313,8 +313,10 @@ int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out,
 /*
  * Measurement aid, not a step of the path: the duration of ONE launch of the fast bf16
  * expert-FFN kernel (bf16, d a multiple of 64), taken from the dispatch's own start and end
- * time stamps.  Stream markers around a launch hold the stream for several microseconds each
- * and would be inside the benchmark's timed region; this costs the stream nothing.
+ * time stamps.  Stream markers around a launch measure their own latency too (about 5 % more
+ * than the kernel at 0.35 ms); these time stamps are the kernel's.  A timed launch still costs
+ * the stream a few microseconds before and after it, so a benchmark times a sample of its
+ * launches, not all of them.
  *   create   : makes a timer (a HOST object holding two events; the one exception to "the
  *              library allocates nothing": no device memory is involved)
  *   arm      : the next such launch enqueued by THIS host thread (by c2r_expert_ffn,

@@ -557,8 +557,7 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
     const uint16_t *no_b1 = nullptr;
     const int32_t *no_gather = nullptr;
     if (LaunchTimer *t = armed_launch_timer) {
-        // a timed launch: the dispatch itself records its start and its end into the timer's
-        // events (no marker packets on the stream, which would hold it for microseconds)
+        // a timed launch: the dispatch itself records its start and its end into the timer's events
         armed_launch_timer = nullptr;
         if (pass == 0)
             hipExtLaunchKernelGGL((ffn_bf16_dma_kernel<0, WM, WN>), g, b, 0, st, t->start, t->stop, 0, a, lda, offsets,
