@@ -109,10 +109,19 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     // (LM A rows + BN B rows), two slices in flight instead of one.
     constexpr int LM = 128, L_A_BYTES = LM * ROWB, L_STAGE_BYTES = (LM + BN) * ROWB, L_NSTAGE = 3;
     constexpr int L_GA = LM / 8 / NW;  // A copy groups per wave on the short path
-    constexpr int SMEM_BYTES = 2 * STAGE_BYTES > L_NSTAGE * L_STAGE_BYTES ? 2 * STAGE_BYTES : L_NSTAGE * L_STAGE_BYTES;
+    // Long path: two stages of A (rows of the activations: shared through L2 by the workgroups of
+    // a tile row, short latency) and a ring of THREE stages of B (rows of the weights: streamed
+    // from HBM, long latency), so that a B slice is copied two slices ahead of its use.
+    constexpr int B_BYTES = BN * ROWB, B_NSTAGE = 3;
+    constexpr int LONG_BYTES = 2 * A_BYTES + B_NSTAGE * B_BYTES;
+    constexpr int SMEM_BYTES = LONG_BYTES > L_NSTAGE * L_STAGE_BYTES ? LONG_BYTES : L_NSTAGE * L_STAGE_BYTES;
+    static_assert(SMEM_BYTES <= 160 * 1024, "one workgroup per CU owns all of its LDS");
     static_assert(LM == TM && (LM / 8) % NW == 0, "the short path is the first wave row's M range");
     __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
-    unsigned char *const st0 = smem, *const st1 = smem + STAGE_BYTES;
+    unsigned char *const st0 = smem, *const st1 = smem + A_BYTES;  // the two A stages
+    // B ring slot q lives at smem + 2*A_BYTES + q*B_BYTES.  Copies and fragment reads address B
+    // as "stage + A_BYTES + ...", so a B slot is handed to them as the pointer A_BYTES below it.
+    unsigned char *bcur = smem + A_BYTES, *bnxt = bcur + B_BYTES, *bwr = bnxt + B_BYTES;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -329,53 +338,50 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     // between the MFMAs is what limits a wave that has a SIMD nearly to itself.
     auto slice_step = [&](int kt, unsigned char *cur, unsigned char *nxt, auto steady) {
         constexpr bool STEADY = decltype(steady)::value;
-#ifndef C2R_CPA
-#define C2R_CPA 4
-#define C2R_CPB 4
-#define C2R_CPC 0
-#define C2R_CPD 0
-#endif
-        static_assert(C2R_CPA + C2R_CPB + C2R_CPC + C2R_CPD == 8, "all pieces scheduled");
+        static_assert(GA == 4 && GB == 4, "pieces 0..3 are the wave's A groups, 4..7 its B groups");
         const bool c1 = STEADY || kt + 1 < nk;
-        const int n1 = c1 ? C2R_CPB : 0, n1b = c1 ? C2R_CPC : 0, n1c = c1 ? C2R_CPD : 0;
-        const int n2 = STEADY || kt + 2 < nk ? C2R_CPA : 0;
+        const int nb = STEADY || kt + 2 < nk ? GB : 0;  // B pieces of slice kt+2, in the first k-step
+        const int na = nb ? GA : 0;                      // A pieces of slice kt+2, after the hand-over
         if (active) {
             // (the first reads of a slice go out after its first two MFMAs: the compiler's wait
             // at the top of the loop body covers every LDS read in flight, and there the only
             // ones in flight should be those the first MFMAs need anyway)
-            C2R_KSTEP(0, 0, 0, kt + 1, nxt, C2R_CPA, n1, read_a(cur, 0, 1, 1));
+            C2R_KSTEP(0, 0, 0, kt + 2, bwr, GA, nb, read_a(cur, 0, 1, 1));
             read_a(cur, 1, 0, 0);
-            read_b(cur, 1, 1);
-            C2R_KSTEP(1, 0, 1, kt + 1, nxt, C2R_CPA + C2R_CPB, n1b, (void)0);
+            read_b(bcur, 1, 1);
+            C2R_KSTEP(1, 0, 1, kt + 2, bwr, NPIECE, 0, (void)0);
             read_a(cur, 1, 1, 1);
-            C2R_KSTEP(0, 1, 0, kt + 1, nxt, C2R_CPA + C2R_CPB + C2R_CPC, n1c, (void)0);
-        } else if (c1) {
-            if (C2R_CPA <= 1) copy_piece(kt + 1, nxt, 1);
-            if (C2R_CPA <= 2) copy_piece(kt + 1, nxt, 2);
-            if (C2R_CPA <= 3) copy_piece(kt + 1, nxt, 3);
-            if (C2R_CPA <= 4) copy_piece(kt + 1, nxt, 4);
-            if (C2R_CPA <= 5) copy_piece(kt + 1, nxt, 5);
-            if (C2R_CPA <= 6) copy_piece(kt + 1, nxt, 6);
-            if (C2R_CPA <= 7) copy_piece(kt + 1, nxt, 7);
+            C2R_KSTEP(0, 1, 0, kt + 2, bwr, NPIECE, 0, (void)0);
+        } else if (nb) {
+            copy_piece(kt + 2, bwr, 4, STEADY);
+            copy_piece(kt + 2, bwr, 5, STEADY);
+            copy_piece(kt + 2, bwr, 6, STEADY);
+            copy_piece(kt + 2, bwr, 7, STEADY);
         }
-        wait_copies_and_lds();  // my copies of slice kt+1 landed, my reads of `cur` returned
+        // my copies of slice kt+1 (A: issued after the previous hand-over, B: a slice earlier
+        // still) have landed once at most the B pieces of slice kt+2 are outstanding; my reads of
+        // this slice's stages have returned
+        if (nb)
+            wait_copies_but_and_lds<GB>();
+        else
+            wait_copies_and_lds();
         lds_barrier();
         if (active) {
             if (c1) {
                 read_a(nxt, 0, 0, 0);
-                read_b(nxt, 0, 0);
+                read_b(bnxt, 0, 0);
             }
-            C2R_KSTEP(1, 1, 1, kt + 2, cur, 0, n2, (void)0);
-        } else if (n2) {
-            copy_piece(kt + 2, cur, 0);
-            if (C2R_CPA > 1) copy_piece(kt + 2, cur, 1);
-            if (C2R_CPA > 2) copy_piece(kt + 2, cur, 2);
-            if (C2R_CPA > 3) copy_piece(kt + 2, cur, 3);
-            if (C2R_CPA > 4) copy_piece(kt + 2, cur, 4);
-            if (C2R_CPA > 5) copy_piece(kt + 2, cur, 5);
-            if (C2R_CPA > 6) copy_piece(kt + 2, cur, 6);
-            if (C2R_CPA > 7) copy_piece(kt + 2, cur, 7);
+            C2R_KSTEP(1, 1, 1, kt + 2, cur, 0, na, (void)0);
+        } else if (na) {
+            copy_piece(kt + 2, cur, 0, STEADY);
+            copy_piece(kt + 2, cur, 1, STEADY);
+            copy_piece(kt + 2, cur, 2, STEADY);
+            copy_piece(kt + 2, cur, 3, STEADY);
         }
+        unsigned char *const freed = bcur;  // every wave has read it: the slot of slice kt+3
+        bcur = bnxt;
+        bnxt = bwr;
+        bwr = freed;
     };
 
     if (short_tile) {
@@ -434,25 +440,25 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         copy_piece(0, st0, 1);
         copy_piece(0, st0, 2);
         copy_piece(0, st0, 3);
-        copy_piece(0, st0, 4);
-        copy_piece(0, st0, 5);
-        copy_piece(0, st0, 6);
-        copy_piece(0, st0, 7);
+        copy_piece(0, bcur, 4);
+        copy_piece(0, bcur, 5);
+        copy_piece(0, bcur, 6);
+        copy_piece(0, bcur, 7);
         wait_copies_but<0>();
         lds_barrier();
         if (nk > 1) {
             copy_piece(1, st1, 0);
-            if (C2R_CPA > 1) copy_piece(1, st1, 1);
-            if (C2R_CPA > 2) copy_piece(1, st1, 2);
-            if (C2R_CPA > 3) copy_piece(1, st1, 3);
-            if (C2R_CPA > 4) copy_piece(1, st1, 4);
-            if (C2R_CPA > 5) copy_piece(1, st1, 5);
-            if (C2R_CPA > 6) copy_piece(1, st1, 6);
-            if (C2R_CPA > 7) copy_piece(1, st1, 7);
+            copy_piece(1, st1, 1);
+            copy_piece(1, st1, 2);
+            copy_piece(1, st1, 3);
+            copy_piece(1, bnxt, 4);
+            copy_piece(1, bnxt, 5);
+            copy_piece(1, bnxt, 6);
+            copy_piece(1, bnxt, 7);
         }
         if (active) {
             read_a(st0, 0, 0, 0);
-            read_b(st0, 0, 0);
+            read_b(bcur, 0, 0);
         }
         int kt = 0;
         for (; kt + 4 < nk; kt += 2) {  // both slices of the pair are followed by two inner slices
