@@ -346,12 +346,16 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             // (the first reads of a slice go out after its first two MFMAs: the compiler's wait
             // at the top of the loop body covers every LDS read in flight, and there the only
             // ones in flight should be those the first MFMAs need anyway)
-            C2R_KSTEP(0, 0, 0, kt + 2, bwr, GA, nb, read_a(cur, 0, 1, 1));
+            // (the B pieces have two slices to land in, so their place is free: measured, the
+            // down pass likes them in the third k-step - away from the A pieces, which follow
+            // the hand-over - by 2-3 %, the gate/up pass in the first by 1 %)
+            constexpr int BSTEP = MODE == 1 ? 2 : 0;
+            C2R_KSTEP(0, 0, 0, kt + 2, bwr, GA, (BSTEP == 0 ? nb : 0), read_a(cur, 0, 1, 1));
             read_a(cur, 1, 0, 0);
             read_b(bcur, 1, 1);
-            C2R_KSTEP(1, 0, 1, kt + 2, bwr, NPIECE, 0, (void)0);
+            C2R_KSTEP(1, 0, 1, kt + 2, bwr, GA, (BSTEP == 1 ? nb : 0), (void)0);
             read_a(cur, 1, 1, 1);
-            C2R_KSTEP(0, 1, 0, kt + 2, bwr, NPIECE, 0, (void)0);
+            C2R_KSTEP(0, 1, 0, kt + 2, bwr, GA, (BSTEP == 2 ? nb : 0), (void)0);
         } else if (nb) {
             copy_piece(kt + 2, bwr, 4, STEADY);
             copy_piece(kt + 2, bwr, 5, STEADY);
