@@ -1,19 +1,21 @@
 // Grouped SwiGLU expert FFN in bf16, fast path: global -> LDS copies that bypass the
 // register file (global_load_lds_dwordx4), 8 waves per workgroup, 256 x 256 output tiles,
-// 64-wide k-slices double buffered in LDS, v_mfma_f32_16x16x32_bf16 (measured 4-8 % faster
+// 64-wide k-slices in LDS (two stages of the activation tile, a ring of three of the weight
+// tile: 160 KB), v_mfma_f32_16x16x32_bf16 (measured 4-8 % faster
 // here than the 32x32x16 form at equal LDS traffic: a quarter of the accumulator registers
 // move per instruction, and under this chip's power limit that buys clock).
 //
 // Same two passes, tile numbering and epilogue as the generic kernel in ffn_bf16.hip;
 // what differs is how a k-slice reaches LDS.  One wave-level copy instruction moves
 // 64 x 16 bytes = 8 tile rows of 128 bytes, i.e. whole cache lines (measured: 128-byte
-// rows copy at ~25 TB/s chip-wide, 64-byte rows at ~16 TB/s, and prefetch depth beyond
-// one slice buys nothing).  Lane l lands at byte 16*l of the 1 KB run, i.e. row l/8, chunk
+// rows copy at ~25 TB/s chip-wide, 64-byte rows at ~16 TB/s).  Lane l lands at byte 16*l of the 1 KB run, i.e. row l/8, chunk
 // position l%8, so the lane fetches the global chunk (l%8) ^ swz_key(row) and the
-// swizzled layout falls out without any LDS write instruction.  The copy of slice k+1
-// is asynchronous and overlaps the MFMAs of slice k; one "my copies landed, my reads
-// returned" wait + bare barrier per slice, placed before the slice's last k-step, hands
-// both stages over (see slice_step).
+// swizzled layout falls out without any LDS write instruction.  The copies are
+// asynchronous and overlap the MFMAs: the A tile of slice k+2 goes out when the stage of
+// slice k is handed over, the B tile of slice k+2 a little earlier into the ring slot of
+// slice k-1 (weights stream from HBM and take longest); one "my copies of the next slice
+// landed, my reads returned" wait + bare barrier per slice, placed before the slice's last
+// k-step, hands the stages over (see slice_step).
 //
 // Contract (checked by the launcher): the contraction length seen by A is padded to a
 // multiple of 64 with zeros (lda >= 64 * ceil(K/64)); a B chunk past K is re-read from
