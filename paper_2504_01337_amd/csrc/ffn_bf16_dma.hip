@@ -116,7 +116,13 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     // from HBM, long latency), so that a B slice is copied two slices ahead of its use.
     constexpr int B_BYTES = BN * ROWB, B_NSTAGE = 3;
     constexpr int LONG_BYTES = 2 * A_BYTES + B_NSTAGE * B_BYTES;
+    // Tiles of at most TM_T rows (experts with a handful of tokens: most of the short tiles) need
+    // even less room for A and get a ring of four stages, three slices in flight: what such a
+    // tile takes is the latency of its weight slices divided by the slices in flight.
+    constexpr int TM_T = 64, T_A_BYTES = TM_T * ROWB, T_STAGE_BYTES = (TM_T + BN) * ROWB, T_NSTAGE = 4;
+    static_assert(TM_T / 8 == NW, "one A copy group per wave on the tiny path");
     constexpr int SMEM_BYTES = LONG_BYTES > L_NSTAGE * L_STAGE_BYTES ? LONG_BYTES : L_NSTAGE * L_STAGE_BYTES;
+    static_assert(T_NSTAGE * T_STAGE_BYTES <= SMEM_BYTES, "the tiny ring fits");
     static_assert(SMEM_BYTES <= 160 * 1024, "one workgroup per CU owns all of its LDS");
     static_assert(LM == TM && (LM / 8) % NW == 0, "the short path is the first wave row's M range");
     __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
@@ -159,6 +165,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     if (rows <= 0) return;
     if (tile_nsub > 1 && rows > BM / tile_nsub) rows = BM / tile_nsub;
     const bool short_tile = rows <= LM;        // workgroup-uniform
+    const bool tiny_tile = rows <= TM_T;
 
     // ---- copy roles: one copy instruction fills 8 tile rows (1024 bytes); lane l lands on
     //      row l/8, chunk position l%8 and therefore fetches chunk (l%8) ^ key(row) ----
@@ -177,7 +184,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     int rowA[GA];
 #pragma unroll
     for (int i = 0; i < GA; ++i) {
-        const int rg = short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
+        const int rg = tiny_tile ? wave : short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
         const int r = rg * 8 + lrow;
         rowA[i] = r < rows ? r : rows - 1;
     }
@@ -192,7 +199,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     }
 #pragma unroll
     for (int i = 0; i < GA; ++i) {
-        const int rg = short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
+        const int rg = tiny_tile ? wave : short_tile ? wave * L_GA + (i < L_GA ? i : 0) : wave * GA + i;
         offA[i] = (uint32_t)rowA[i] * (uint32_t)lda * 2u + (uint32_t)chunkc[rg & 1] * 16u;
     }
 #pragma unroll
@@ -255,7 +262,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             r = (j < FN16 / 2) ? wn * (TN / 2) + j * 16 : BN / 2 + wn * (TN / 2) + (j - FN16 / 2) * 16;
         else
             r = wn * TN + j * 16;
-        rdB[j] = (uint32_t)(short_tile ? L_A_BYTES : A_BYTES) + (uint32_t)(r + fr) * ROWB;
+        rdB[j] = (uint32_t)(tiny_tile ? T_A_BYTES : short_tile ? L_A_BYTES : A_BYTES) + (uint32_t)(r + fr) * ROWB;
     }
     const int sw = swz_key(fr);
     // waves whose whole M range lies past the group's end only help with the copies
@@ -390,7 +397,49 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         bwr = freed;
     };
 
-    if (short_tile) {
+    if (tiny_tile) {
+        // ---- tiny tile: four-stage ring, three slices in flight, one barrier per slice ----
+        static_assert(GB == 4, "five copies per wave per slice below");
+        auto tiny_copy = [&](int kt) {
+            unsigned char *stage = smem + (kt & (T_NSTAGE - 1)) * T_STAGE_BYTES;
+            const uint32_t kb = (uint32_t)kt * ROWB;
+            copy16_to_lds(baseA + kb, offA[0], stage + wave * 1024);
+            const bool last = ktail && kt == nk - 1;
+            const bool clamp0 = last && kt * BK + chunkc[0] * 8 >= Kdim, clamp1 = last && kt * BK + chunkc[1] * 8 >= Kdim;
+            unsigned char *sb = stage + T_A_BYTES + wave * GB * 1024;
+            copy16_to_lds(baseB, clamp0 ? rowB[0] : offB[0] + kb, sb);
+            copy16_to_lds(baseB, clamp1 ? rowB[1] : offB[1] + kb, sb + 1024);
+            copy16_to_lds(baseB, clamp0 ? rowB[2] : offB[2] + kb, sb + 2048);
+            copy16_to_lds(baseB, clamp1 ? rowB[3] : offB[3] + kb, sb + 3072);
+        };
+        const int nf = (rows + 15) >> 4;  // 1..4 fragments of 16 rows hold rows of the group
+        tiny_copy(0);
+        if (nk > 1) tiny_copy(1);
+        if (nk > 2) tiny_copy(2);
+        for (int kt = 0; kt < nk; ++kt) {
+            // slice kt has landed once at most the copies of slices kt+1 and kt+2 are outstanding
+            if (kt + 2 < nk)
+                wait_copies_but_and_lds<10>();
+            else if (kt + 1 < nk)
+                wait_copies_but_and_lds<5>();
+            else
+                wait_copies_but_and_lds<0>();
+            lds_barrier();  // every wave's reads of slice kt-1 have returned: its stage is free
+            if (kt + 3 < nk) tiny_copy(kt + 3);
+            if (wm == 0) {
+                const unsigned char *stage = smem + (kt & (T_NSTAGE - 1)) * T_STAGE_BYTES;
+#pragma unroll
+                for (int kq = 0; kq < 2; ++kq) {
+                    read_b(stage, kq, 0);
+                    read_a_first(stage, kq, 0, 0, nf);
+                    C2R_MFMA_ROW(0, 0, 0, 0);
+                    if (nf > 1) { C2R_MFMA_ROW(0, 0, 0, 1); }
+                    if (nf > 2) { C2R_MFMA_ROW(0, 0, 0, 2); }
+                    if (nf > 3) { C2R_MFMA_ROW(0, 0, 0, 3); }
+                }
+            }
+        }
+    } else if (short_tile) {
         // ---- short tile: three-stage ring, two slices in flight, one barrier per slice ----
         static_assert(L_GA == 2 && GB == 4, "six copies per wave per slice below");
         auto short_copy = [&](int kt) {
