@@ -499,8 +499,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         copy_piece(0, bcur, 5);
         copy_piece(0, bcur, 6);
         copy_piece(0, bcur, 7);
-        wait_copies_but<0>();
-        lds_barrier();
+        // every stage is free at the start of a tile: slice 1 goes out right behind slice 0
         if (nk > 1) {
             copy_piece(1, st1, 0);
             copy_piece(1, st1, 1);
@@ -510,7 +509,11 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
             copy_piece(1, bnxt, 5);
             copy_piece(1, bnxt, 6);
             copy_piece(1, bnxt, 7);
+            wait_copies_but<8>();  // slice 0 has landed
+        } else {
+            wait_copies_but<0>();
         }
+        lds_barrier();
         if (active) {
             read_a(st0, 0, 0, 0);
             read_b(bcur, 0, 0);
