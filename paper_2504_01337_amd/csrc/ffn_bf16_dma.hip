@@ -287,7 +287,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) bset[set][j] = *reinterpret_cast<const bf16x8 *>(stage + rdB[j] + ch);
     };
-    static_assert(NPIECE == 8, "copy schedule below: 4 + 4 pieces over two k-steps");
+    static_assert(NPIECE == 8, "copy schedule below: the A pieces in one k-step, the B pieces in another");
     // MFMAs of one k-step (operands swapped: the lane's 4 results lie along n) with up to
     // eight copy pieces P0.. of slice CKT slipped in after every second MFMA.  Macros, so that
     // every fragment and piece index is a literal and the arrays stay in registers.
@@ -335,13 +335,13 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
 
     // One 64-wide slice = four k-steps.  The hand-over barrier sits before the LAST k-step:
     // by then the copy of the next slice has landed and every wave has finished reading this
-    // slice's stage.  After it, the copy of the slice after next starts going into this stage
-    // (4 pieces in the last k-step here, 4 in the first k-step of the next slice, one after
-    // every second MFMA: as early as the stage allows, so that they have landed well before
-    // the next barrier; measured 3.5 % faster per step than 3 + 3 + 2 pieces spread one per
-    // four MFMAs over three k-steps), and the first fragments
-    // of the next slice are read while the last k-step's MFMAs run, so the MFMA stream
-    // never starts a slice by waiting on LDS.
+    // slice's stages.  After it, the A tile of the slice after next starts going into the A
+    // stage just handed over (the wave's 4 A pieces in the last k-step, one after every second
+    // MFMA: as early as the stage allows, they have one slice to land in), and the first
+    // fragments of the next slice are read while the last k-step's MFMAs run, so the MFMA
+    // stream never starts a slice by waiting on LDS.  The B tile of the slice after next goes
+    // into the ring slot that the slice BEFORE this one used, free since the previous
+    // hand-over (the wave's 4 B pieces in one of the first three k-steps).
     // `steady` (a compile-time flag): kt + 3 < nk, i.e. both following slices exist and neither
     // is the last, so every copy is unconditional and unclamped: the instruction stream
     // between the MFMAs is what limits a wave that has a SIMD nearly to itself.
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
         constexpr bool STEADY = decltype(steady)::value;
         static_assert(GA == 4 && GB == 4, "pieces 0..3 are the wave's A groups, 4..7 its B groups");
         const bool c1 = STEADY || kt + 1 < nk;
-        const int nb = STEADY || kt + 2 < nk ? GB : 0;  // B pieces of slice kt+2, in the first k-step
+        const int nb = STEADY || kt + 2 < nk ? GB : 0;  // B pieces of slice kt+2, before the hand-over
         const int na = nb ? GA : 0;                      // A pieces of slice kt+2, after the hand-over
         if (active) {
             // (the first reads of a slice go out after its first two MFMAs: the compiler's wait
