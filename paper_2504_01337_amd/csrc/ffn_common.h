@@ -160,14 +160,19 @@ static inline int64_t xcd_grouped_grid(int64_t mtiles_bound, int ntn, bool split
 // a chunk held 2-3 small experts and streamed all of their weights: measured 2.2 x the
 // weight bytes at the Qwen-MoE shape).  Each XCD gets a contiguous range of tile numbers of
 // equal estimated COST, not equal count: an M-tile of at most BM/2 rows (only an expert's
-// last one can be) runs the short path at about half the time of a full one, and ranges of
-// equal count were measured 6 % apart in cost on Zipf-sized experts.  A boundary moves at
+// last one can be) runs the short path, which is bound by streaming the expert's weights and
+// counted as two thirds of a full tile (weights 3 : 2 measured 0.5-1 % faster per pass than
+// 2 : 1, 3 : 1 and 1 : 1), and ranges of equal count were measured 6 % apart in cost on
+// Zipf-sized experts.  A boundary moves at
 // most 1/64 of the tiles away from its equal-count position, which bounds the workgroups a
 // launch needs (ragged_grid) without knowing the group sizes on the host.
+// estimated cost of an M-tile: full, and an expert's last one if it has at most BM/2 rows
+#define C2R_COST_FULL 3
+#define C2R_COST_SHORT 2
 struct RaggedMap {
     int lo, hi;        // this lane's expert: row range (clamped to [0, A_cap])
     int tiles, first;  // its M-tiles and its first M-tile number
-    int cost, pcost;   // 2 per M-tile, 1 for a short last one; exclusive prefix over experts
+    int cost, pcost;   // C2R_COST_FULL per M-tile, C2R_COST_SHORT for a short last one; exclusive prefix over experts
     int total_mtiles, total_cost;  // wave-uniform
 };
 
@@ -182,7 +187,7 @@ __device__ __forceinline__ RaggedMap build_ragged_map(const int32_t *__restrict_
     m.total_mtiles = gm.total_mtiles;
     const int cnt = gm.hi - gm.lo;
     const bool short_last = gm.tiles > 0 && cnt - (gm.tiles - 1) * BM <= BM / 2;
-    m.cost = 2 * gm.tiles - (short_last ? 1 : 0);
+    m.cost = C2R_COST_FULL * gm.tiles - (short_last ? C2R_COST_FULL - C2R_COST_SHORT : 0);
     const int incl = wave_inclusive_scan(m.cost);
     m.pcost = incl - m.cost;
     m.total_cost = __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
@@ -205,14 +210,14 @@ __device__ __forceinline__ int ragged_boundary(const RaggedMap &m, int ntn, int 
     const int tiles = __builtin_amdgcn_readlane(m.tiles, e), first = __builtin_amdgcn_readlane(m.first, e);
     const int cost = __builtin_amdgcn_readlane(m.cost, e), pc = __builtin_amdgcn_readlane(m.pcost, e);
     const uint32_t r = g - (uint32_t)ntn * (uint32_t)pc;  // cost offset inside the expert
-    const int sh = 2 * tiles - cost;                       // 1: the last M-tile is short
+    const int sh = C2R_COST_FULL * tiles - cost;           // > 0: the last M-tile is short (full - short cost)
     const int gl = tiles - TILE_GM * ((tiles - 1) / TILE_GM);  // M-tiles of the last chunk
-    const uint32_t R = 2u * (uint32_t)(tiles - gl) * (uint32_t)ntn;  // cost of the full chunks
+    const uint32_t R = (uint32_t)C2R_COST_FULL * (uint32_t)(tiles - gl) * (uint32_t)ntn;  // cost of the full chunks
     uint32_t t;
     if (r < R)
-        t = r / 2u;
+        t = r / (uint32_t)C2R_COST_FULL;
     else  // the last chunk's tiles cost (2 gl - sh) / gl on average (its M-tiles alternate)
-        t = (uint32_t)(tiles - gl) * (uint32_t)ntn + (r - R) * (uint32_t)gl / (uint32_t)(2 * gl - sh);
+        t = (uint32_t)(tiles - gl) * (uint32_t)ntn + (r - R) * (uint32_t)gl / (uint32_t)(C2R_COST_FULL * gl - sh);
     const int b = first * ntn + (int)t;
     return b < even - win ? even - win : (b > even + win ? even + win : b);
 }
