@@ -1,9 +1,11 @@
 // Router logits (Eq. 1) and collaboration-constrained selection (Sec. 3.3, step 2).
 //
 // Two kernels.
-//  route_partial_kernel: a register-tiled fp32 GEMM over one 256-long k-chunk; every
-//    (token, expert) pair belongs to one thread, which accumulates it with one fma per k
-//    in ascending k - exactly the ABI's declared order.  Chunk results go to scratch as
+//  route_partial_kernel: an fp32 GEMM over one 256-long k-chunk in which every (token,
+//    expert) sum is built with one fused multiply-add per k in ascending k - exactly the
+//    ABI's declared order - either by one thread on the vector pipe (up to 8 experts) or by
+//    a chain of v_mfma_f32_32x32x2_f32 on the matrix pipe, whose two products per
+//    instruction are added in that same order.  Chunk results go to scratch as
 //    part[tile][chunk][expert][64] (token fastest, one tile's partials contiguous).
 //  route_select_kernel: lane = token.  Adds the chunk results left to right, adds the
 //    bias, then does arg max / masked top-(K-1) entirely in registers with one 64-bit
@@ -31,7 +33,14 @@ __global__ __launch_bounds__(256) void pack_router_kernel(const float *__restric
 // loads held in registers; the W sub-tile is shared by the workgroup's waves.
 // TQ = 4 halves a wave's tile: twice the waves for batches that would otherwise leave one wave
 // per SIMD with nothing to hide its LDS latency behind.
-template <bool BF16, int TE, int NWV, int TQ>
+//
+// MFMA = true does the same sums on the matrix pipe: one v_mfma_f32_32x32x2_f32 adds, to each of
+// 32 experts x 32 tokens, the products of k and k+1 - as two fused multiply-adds, k first,
+// then k+1, each rounded to nearest even (checked on the chip against chains of fmaf: bit
+// identical, denormal and overflow ranges included), so a chain of them over ascending k IS
+// the declared order, at twice the rate the vector pipe reaches without packed instructions.
+// Lanes 0-31 feed k, lanes 32-63 k+1: one W value and one x value per lane and instruction.
+template <bool BF16, int TE, int NWV, int TQ, bool MFMA>
 __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__restrict__ x,
                                                                 const float *__restrict__ W, int ldw,
                                                                 int ep, int64_t T, int d, int nchunk,
@@ -65,9 +74,16 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
     const int64_t t0 = wt * TOK;
     const unsigned char *xb = static_cast<const unsigned char *>(x);
 
-    float4 wreg[WLOADS];
-    uint4 xreg[XLOADS];
-    auto gload = [&](int k0) {
+    // global loads of a sub-tile are held in registers until its LDS buffer is free; two sets, so
+    // that a sub-tile is fetched two sub-tiles ahead (on the matrix pipe one sub-tile of compute
+    // is shorter than the memory latency)
+    struct Staged {
+        float4 w[WLOADS];
+        uint4 x[XLOADS];
+    };
+    auto gload = [&](Staged &r, int k0) __attribute__((always_inline)) {
+        float4 (&wreg)[WLOADS] = r.w;
+        uint4 (&xreg)[XLOADS] = r.x;
 #pragma unroll
         for (int i = 0; i < WLOADS; ++i) {
             const int idx = tid + i * NWV * 64;
@@ -88,7 +104,9 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
             if (kc < k_end) xreg[i] = *reinterpret_cast<const uint4 *>(xb + ((size_t)t * d + kc) * ESZ);
         }
     };
-    auto lstore = [&](int buf) {
+    auto lstore = [&](const Staged &r, int buf) __attribute__((always_inline)) {
+        const float4 (&wreg)[WLOADS] = r.w;
+        const uint4 (&xreg)[XLOADS] = r.x;
 #pragma unroll
         for (int i = 0; i < WLOADS; ++i) {
             const int idx = tid + i * NWV * 64;
@@ -101,20 +119,80 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
         }
     };
 
+    typedef float f32x16 __attribute__((ext_vector_type(16)));
+    constexpr int NEB = MFMA ? EPAD / 32 : 1, NTB = MFMA ? TOK / 32 : 1;  // 32-expert / 32-token blocks
+    static_assert(!MFMA || (EPAD % 32 == 0 && TOK % 32 == 0), "whole 32 x 32 blocks");
+    f32x16 macc[NEB][NTB];
+#pragma unroll
+    for (int a = 0; a < NEB; ++a)
+#pragma unroll
+        for (int b = 0; b < NTB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) macc[a][b][i] = 0.0f;
+    const int mh = lane >> 5, mc = lane & 31;  // k parity and block column fed by this lane
     float acc[TQ][TE];
 #pragma unroll
     for (int q = 0; q < TQ; ++q)
 #pragma unroll
         for (int j = 0; j < TE; ++j) acc[q][j] = 0.0f;
 
-    gload(k_begin);
-    lstore(0);
-    __syncthreads();
-    int buf = 0;
-    for (int k0 = k_begin; k0 < k_end; k0 += KS) {
-        const int knext = k0 + KS;
-        if (knext < k_end) gload(knext);
+    auto compute = [&](int buf, int k0) __attribute__((always_inline)) {
         const int nvec = min(KS, k_end - k0) / VEC;  // workgroup-uniform
+        if constexpr (MFMA) {
+            auto pair = [&](int kp) __attribute__((always_inline)) {
+                float wv[NEB], xv[NTB];
+#pragma unroll
+                for (int a = 0; a < NEB; ++a) wv[a] = Wl[buf][2 * kp + mh][a * 32 + mc];
+#pragma unroll
+                for (int b = 0; b < NTB; ++b) {
+                    const unsigned char *row = &Xl[buf][wave][(b * 32 + mc) * XPITCH];
+                    if (BF16) {  // one word holds x[k] (low half) and x[k+1] (high half)
+                        const uint32_t word = *reinterpret_cast<const uint32_t *>(row + kp * 4);
+                        xv[b] = __uint_as_float(mh ? (word & 0xffff0000u) : (word << 16));
+                    } else {
+                        xv[b] = *reinterpret_cast<const float *>(row + (2 * kp + mh) * 4);
+                    }
+                }
+#pragma unroll
+                for (int a = 0; a < NEB; ++a)
+#pragma unroll
+                    for (int b = 0; b < NTB; ++b)
+                        macc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[a], xv[b], macc[a][b], 0, 0, 0);
+            };
+            const int npair = nvec * VEC / 2;
+            if (npair == KS / 2) {
+                // a whole sub-tile: every operand is read first, into registers of its own, so that
+                // the matrix instructions never wait for a read issued just before them
+                float wv[KS / 2][NEB], xv[KS / 2][NTB];
+#pragma unroll
+                for (int kp = 0; kp < KS / 2; ++kp)
+#pragma unroll
+                    for (int a = 0; a < NEB; ++a) wv[kp][a] = Wl[buf][2 * kp + mh][a * 32 + mc];
+#pragma unroll
+                for (int b = 0; b < NTB; ++b) {
+                    const unsigned char *row = &Xl[buf][wave][(b * 32 + mc) * XPITCH];
+#pragma unroll
+                    for (int kp = 0; kp < KS / 2; ++kp) {
+                        if (BF16) {
+                            const uint32_t word = *reinterpret_cast<const uint32_t *>(row + kp * 4);
+                            xv[kp][b] = __uint_as_float(mh ? (word & 0xffff0000u) : (word << 16));
+                        } else {
+                            xv[kp][b] = *reinterpret_cast<const float *>(row + (2 * kp + mh) * 4);
+                        }
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);  // (the scheduler would sink each read to its use)
+#pragma unroll
+                for (int kp = 0; kp < KS / 2; ++kp)
+#pragma unroll
+                    for (int a = 0; a < NEB; ++a)
+#pragma unroll
+                        for (int b = 0; b < NTB; ++b)
+                            macc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(wv[kp][a], xv[kp][b], macc[a][b], 0, 0, 0);
+            } else {
+                for (int kp = 0; kp < npair; ++kp) pair(kp);
+            }
+        } else
         for (int v = 0; v < nvec; ++v) {
             uint4 xp[TQ];
 #pragma unroll
@@ -136,13 +214,40 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
                 }
             }
         }
-        if (knext < k_end) lstore(buf ^ 1);
+    };
+    Staged r0, r1;
+    gload(r0, k_begin);
+    lstore(r0, 0);
+    if (k_begin + KS < k_end) gload(r1, k_begin + KS);
+    if (k_begin + 2 * KS < k_end) gload(r0, k_begin + 2 * KS);
+    __syncthreads();
+    for (int k0 = k_begin; k0 < k_end; k0 += 2 * KS) {
+        compute(0, k0);
+        if (k0 + KS < k_end) lstore(r1, 1);
+        if (k0 + 3 * KS < k_end) gload(r1, k0 + 3 * KS);
         __syncthreads();
-        buf ^= 1;
+        if (k0 + KS >= k_end) break;
+        compute(1, k0 + KS);
+        if (k0 + 2 * KS < k_end) lstore(r0, 0);
+        if (k0 + 4 * KS < k_end) gload(r0, k0 + 4 * KS);
+        __syncthreads();
     }
     if (!live) return;
     const int64_t tile = wt / (64 / TOK);           // the 64-token tile and this wave's part of it
     float *dst = part + (((size_t)tile * nchunk + chunk) * ep) * 64 + (wt % (64 / TOK)) * TOK;
+    if constexpr (MFMA) {
+        // register i of a 32 x 32 block: expert (i/4)*8 + 4*(lane/32) + i%4, token lane%32
+#pragma unroll
+        for (int a = 0; a < NEB; ++a)
+#pragma unroll
+            for (int b = 0; b < NTB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int e = a * 32 + (i / 4) * 8 + mh * 4 + i % 4;
+                    if (e < ep) dst[(size_t)e * 64 + b * 32 + mc] = macc[a][b][i];
+                }
+        return;
+    }
 #pragma unroll
     for (int j = 0; j < TE; ++j) {
         const int e = el * TE + j;
@@ -387,22 +492,24 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
     const int64_t ntiles = L.Tpad / 64;
     // Four waves per workgroup share the W sub-tiles.  A batch with fewer than two 64-token
     // wave tiles per SIMD of the chip uses half-size wave tiles: with one wave per SIMD nothing
-    // hides its LDS latency (measured at T = 8192, d = 2048, E = 60: 54 -> 43 us).
+    // hides its latencies (measured at T = 8192, d = 2048, E = 60 on the vector pipe: 54 -> 42 us;
+    // on the matrix pipe the kernel then takes 31 us).
     const int te = L.EP > 32 ? 8 : L.EP > 16 ? 4 : L.EP > 8 ? 2 : 1;
     const bool wide = ntiles * L.nchunk >= 2048;
     constexpr int NWV = 4;
     const int64_t nwt = wide ? ntiles : ntiles * 2;
     const int64_t nblk = (nwt + NWV - 1) / NWV * L.nchunk;
     if (nblk >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
-#define C2R_ROUTE_LAUNCH(BF, TE, NWV, TQ)                                                         \
-    route_partial_kernel<BF, TE, NWV, TQ><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(        \
+    // more than 8 experts: the matrix pipe, a wave covering 32 or 64 experts (padded with zero columns)
+#define C2R_ROUTE_LAUNCH(BF, TE, NWV, TQ, MF)                                                     \
+    route_partial_kernel<BF, TE, NWV, TQ, MF><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(    \
         x, W, ldw, L.EP, T, d, L.nchunk, ntiles, part)
-#define C2R_ROUTE_TE(BF, NWV, TQ)                          \
-    switch (te) {                                          \
-        case 8: C2R_ROUTE_LAUNCH(BF, 8, NWV, TQ); break;   \
-        case 4: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ); break;   \
-        case 2: C2R_ROUTE_LAUNCH(BF, 2, NWV, TQ); break;   \
-        default: C2R_ROUTE_LAUNCH(BF, 1, NWV, TQ); break;  \
+#define C2R_ROUTE_TE(BF, NWV, TQ)                                 \
+    switch (te) {                                                 \
+        case 8: C2R_ROUTE_LAUNCH(BF, 8, NWV, TQ, true); break;    \
+        case 4: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ, true); break;    \
+        case 2: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ, true); break;    \
+        default: C2R_ROUTE_LAUNCH(BF, 1, NWV, TQ, false); break;  \
     }
     if (x_dt == C2R_BF16) {
         if (wide) { C2R_ROUTE_TE(true, NWV, 8) } else { C2R_ROUTE_TE(true, NWV, 4) }
