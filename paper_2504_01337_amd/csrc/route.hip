@@ -12,6 +12,8 @@
 //    collaborator mask per expert held in LDS.
 #include "c2r_internal.h"
 
+#include <type_traits>
+
 namespace c2r {
 
 // Wp[k][j] = W_g[k][j] zero-padded to a row length that is a multiple of 4 (only needed when
@@ -41,7 +43,7 @@ __global__ __launch_bounds__(256) void pack_router_kernel(const float *__restric
 // the declared order, at twice the rate the vector pipe reaches without packed instructions.
 // Lanes 0-31 feed k, lanes 32-63 k+1: one W value and one x value per lane and instruction.
 template <bool BF16, int TE, int NWV, int TQ, bool MFMA>
-__global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__restrict__ x,
+__global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_partial_kernel(const void *__restrict__ x,
                                                                 const float *__restrict__ W, int ldw,
                                                                 int ep, int64_t T, int d, int nchunk,
                                                                 int64_t ntiles,
@@ -57,8 +59,13 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
     static_assert(XLOADS >= 1 && 64 % TOK == 0, "a wave loads whole vectors; wave tiles divide the 64-token tile");
     constexpr int WF4 = KS * EPAD / 4;     // float4 per W sub-tile
     constexpr int WLOADS = (WF4 + NWV * 64 - 1) / (NWV * 64);
-    __shared__ __attribute__((aligned(16))) float Wl[2][KS][EPAD];
-    __shared__ __attribute__((aligned(16))) unsigned char Xl[2][NWV][TOK * XPITCH];
+    // One wave's matrix instructions of a sub-tile overlap its own operand reads of the next one
+    // (PIPE): that takes a third LDS buffer and two operand register sets, which fit 32-token
+    // wave tiles only.
+    constexpr bool PIPE = MFMA && TOK == 32;
+    constexpr int NBUF = PIPE ? 3 : 2;
+    __shared__ __attribute__((aligned(16))) float Wl[NBUF][KS][EPAD];
+    __shared__ __attribute__((aligned(16))) unsigned char Xl[NBUF][NWV][TOK * XPITCH];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -77,20 +84,25 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
     // global loads of a sub-tile are held in registers until its LDS buffer is free; two sets, so
     // that a sub-tile is fetched two sub-tiles ahead (on the matrix pipe one sub-tile of compute
     // is shorter than the memory latency)
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     struct Staged {
-        float4 w[WLOADS];
-        uint4 x[XLOADS];
+        f32x4 w[WLOADS];
+        u32x4 x[XLOADS];
     };
+    // Every load is issued, out-of-range ones on a clamped address: with no branch around a
+    // load the compiler counts the loads in flight and waits only for the older set.  What a
+    // clamped load brings is never used: k past the end of the chunk is left out by the
+    // compute loops, experts >= ep and tokens >= T are accumulated and never stored or read.
     auto gload = [&](Staged &r, int k0) __attribute__((always_inline)) {
-        float4 (&wreg)[WLOADS] = r.w;
-        uint4 (&xreg)[XLOADS] = r.x;
+        f32x4 (&wreg)[WLOADS] = r.w;
+        u32x4 (&xreg)[XLOADS] = r.x;
 #pragma unroll
         for (int i = 0; i < WLOADS; ++i) {
             const int idx = tid + i * NWV * 64;
             const int k = idx / (EPAD / 4), c = idx % (EPAD / 4);
-            wreg[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (idx < WF4 && k0 + k < k_end && c * 4 < ep)
-                wreg[i] = *reinterpret_cast<const float4 *>(W + (size_t)(k0 + k) * ldw + c * 4);
+            const int kk = min(k0 + k, k_end - 1), cc = c * 4 < ep ? c : 0;
+            wreg[i] = *reinterpret_cast<const f32x4 *>(W + (size_t)kk * ldw + cc * 4);
         }
 #pragma unroll
         for (int i = 0; i < XLOADS; ++i) {
@@ -99,23 +111,46 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
             int64_t t = t0 + tok;
             t = t < T ? t : T - 1;  // rows past the end (and dead waves) re-read a valid token
             t = t < 0 ? 0 : t;
-            const int kc = k0 + c * VEC;
-            xreg[i] = make_uint4(0, 0, 0, 0);
-            if (kc < k_end) xreg[i] = *reinterpret_cast<const uint4 *>(xb + ((size_t)t * d + kc) * ESZ);
+            const int kc = min(k0 + c * VEC, k_end - VEC);
+            xreg[i] = *reinterpret_cast<const u32x4 *>(xb + ((size_t)t * d + kc) * ESZ);
         }
     };
+    // The same loads of a whole sub-tile (nothing to clamp in k): a uniform base per sub-tile
+    // plus a 32-bit lane offset that is the same for every sub-tile.
+    uint32_t woff[WLOADS], xoff[XLOADS];
+#pragma unroll
+    for (int i = 0; i < WLOADS; ++i) {
+        const int idx = tid + i * NWV * 64;
+        const int k = min(idx / (EPAD / 4), KS - 1), c = idx % (EPAD / 4);
+        woff[i] = (uint32_t)((k * ldw + (c * 4 < ep ? c * 4 : 0)) * 4);
+    }
+    const int64_t tb = t0 < T ? t0 : T - 1;  // wave-uniform; dead waves re-read valid tokens
+#pragma unroll
+    for (int i = 0; i < XLOADS; ++i) {
+        const int idx = lane + i * 64;
+        const int64_t room = T - 1 - tb, tok = idx / XV < room ? idx / XV : room;
+        xoff[i] = (uint32_t)((tok * d + (idx % XV) * VEC) * ESZ);
+    }
+    auto gload_whole = [&](Staged &r, int k0) __attribute__((always_inline)) {
+        const unsigned char *wb = reinterpret_cast<const unsigned char *>(W + (size_t)k0 * ldw);
+        const unsigned char *xs = xb + ((size_t)tb * d + k0) * ESZ;
+#pragma unroll
+        for (int i = 0; i < WLOADS; ++i) r.w[i] = *reinterpret_cast<const f32x4 *>(wb + woff[i]);
+#pragma unroll
+        for (int i = 0; i < XLOADS; ++i) r.x[i] = *reinterpret_cast<const u32x4 *>(xs + xoff[i]);
+    };
     auto lstore = [&](const Staged &r, int buf) __attribute__((always_inline)) {
-        const float4 (&wreg)[WLOADS] = r.w;
-        const uint4 (&xreg)[XLOADS] = r.x;
+        const f32x4 (&wreg)[WLOADS] = r.w;
+        const u32x4 (&xreg)[XLOADS] = r.x;
 #pragma unroll
         for (int i = 0; i < WLOADS; ++i) {
             const int idx = tid + i * NWV * 64;
-            if (idx < WF4) *reinterpret_cast<float4 *>(&Wl[buf][idx / (EPAD / 4)][(idx % (EPAD / 4)) * 4]) = wreg[i];
+            if (WF4 % (NWV * 64) == 0 || idx < WF4) *reinterpret_cast<f32x4 *>(&Wl[buf][idx / (EPAD / 4)][(idx % (EPAD / 4)) * 4]) = wreg[i];
         }
 #pragma unroll
         for (int i = 0; i < XLOADS; ++i) {
             const int idx = lane + i * 64;
-            *reinterpret_cast<uint4 *>(&Xl[buf][wave][(idx / XV) * XPITCH + (idx % XV) * 16]) = xreg[i];
+            *reinterpret_cast<u32x4 *>(&Xl[buf][wave][(idx / XV) * XPITCH + (idx % XV) * 16]) = xreg[i];
         }
     };
 
@@ -215,22 +250,99 @@ __global__ __launch_bounds__(NWV * 64) void route_partial_kernel(const void *__r
             }
         }
     };
+    bool piped = false;
+    if constexpr (PIPE) {
+        // Sub-tile i: operands in registers (set i % 2); sub-tile i+1: in LDS buffer (i+1) % 3;
+        // sub-tile i+2: on its way from the staging registers into buffer (i+2) % 3; sub-tiles
+        // i+3 and i+4: global loads in flight.  The chain of every accumulator still takes k in
+        // ascending order, two per instruction.
+        struct Ops {
+            float w[KS / 2][NEB];
+            uint32_t x[KS / 2][NTB];
+        };
+        auto read_ops = [&](Ops &o, int buf) __attribute__((always_inline)) {
+#pragma unroll
+            for (int kp = 0; kp < KS / 2; ++kp)
+#pragma unroll
+                for (int a = 0; a < NEB; ++a) o.w[kp][a] = Wl[buf][2 * kp + mh][a * 32 + mc];
+#pragma unroll
+            for (int b = 0; b < NTB; ++b) {
+                const unsigned char *row = &Xl[buf][wave][(b * 32 + mc) * XPITCH];
+#pragma unroll
+                for (int kp = 0; kp < KS / 2; ++kp)  // bf16: the word holds x[k] (low) and x[k+1] (high)
+                    o.x[kp][b] = *reinterpret_cast<const uint32_t *>(row + (BF16 ? kp : 2 * kp + mh) * 4);
+            }
+        };
+        const int sh = mh ? 0 : 16;
+        auto mma = [&](const Ops &o) __attribute__((always_inline)) {
+#pragma unroll
+            for (int kp = 0; kp < KS / 2; ++kp)
+#pragma unroll
+                for (int b = 0; b < NTB; ++b) {
+                    const float xv = __uint_as_float(BF16 ? (o.x[kp][b] << sh) & 0xffff0000u : o.x[kp][b]);
+#pragma unroll
+                    for (int a = 0; a < NEB; ++a)
+                        macc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(o.w[kp][a], xv, macc[a][b], 0, 0, 0);
+                }
+        };
+        // Whole chunks only, and the sub-tile loop unrolled into straight-line code: only there
+        // does the compiler count the loads in flight exactly, so that a wait for the older
+        // staging set leaves the younger one in flight.  (A ragged last chunk takes the loop below.)
+        constexpr int NSUB = C2R_CANON_CHUNK / KS;
+        static_assert(NSUB >= 5, "the prologue fetches sub-tiles 0 to 4");
+        if (k_end - k_begin == C2R_CANON_CHUNK) {
+            // sub-tile j waits in staging set j % 3; the first three are requested together
+            Staged R[3];
+            Ops O[2];
+            gload_whole(R[0], k_begin);
+            gload_whole(R[1], k_begin + KS);
+            gload_whole(R[2], k_begin + 2 * KS);
+            lstore(R[0], 0);
+            gload_whole(R[0], k_begin + 3 * KS);
+            __syncthreads();
+            read_ops(O[0], 0);
+            lstore(R[1], 1);
+            gload_whole(R[1], k_begin + 4 * KS);
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < NSUB; ++i) {
+                if (i + 1 < NSUB) read_ops(O[(i + 1) & 1], (i + 1) % 3);
+                if (i + 2 < NSUB) lstore(R[(i + 2) % 3], (i + 2) % 3);
+                if (i + 5 < NSUB) gload_whole(R[(i + 2) % 3], k_begin + (i + 5) * KS);
+                mma(O[i & 1]);
+                // the step's memory instructions go between its matrix instructions, one each:
+                // the wave issues them while the matrix pipe works
+#pragma unroll
+                for (int m = 0; m < NEB * NTB * KS / 2; ++m) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // a matrix instruction
+                    if (m < 20) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);       // an LDS read
+                    else if (m < 24) __builtin_amdgcn_sched_group_barrier(0x200, 1, 0);  // an LDS write
+                    else if (m < 28) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);  // a global load
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                if (i + 1 < NSUB) __syncthreads();
+            }
+            piped = true;
+        }
+    }
+    if (!piped) {
     Staged r0, r1;
     gload(r0, k_begin);
     lstore(r0, 0);
-    if (k_begin + KS < k_end) gload(r1, k_begin + KS);
-    if (k_begin + 2 * KS < k_end) gload(r0, k_begin + 2 * KS);
+    gload(r1, k_begin + KS);  // (past the end of the chunk: clamped loads, never stored)
+    gload(r0, k_begin + 2 * KS);
     __syncthreads();
     for (int k0 = k_begin; k0 < k_end; k0 += 2 * KS) {
         compute(0, k0);
         if (k0 + KS < k_end) lstore(r1, 1);
-        if (k0 + 3 * KS < k_end) gload(r1, k0 + 3 * KS);
+        gload(r1, k0 + 3 * KS);
         __syncthreads();
         if (k0 + KS >= k_end) break;
         compute(1, k0 + KS);
         if (k0 + 2 * KS < k_end) lstore(r0, 0);
-        if (k0 + 4 * KS < k_end) gload(r0, k0 + 4 * KS);
+        gload(r0, k0 + 4 * KS);
         __syncthreads();
+    }
     }
     if (!live) return;
     const int64_t tile = wt / (64 / TOK);           // the 64-token tile and this wave's part of it
