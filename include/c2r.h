@@ -108,7 +108,9 @@ int c2r_collaborators(const int32_t *C, int E, int Tc, int32_t *collab_idx, uint
  *   slot 0      = arg max_e l[t, e] over ALL experts (ties: lower index);
  *   slots 1..K-1 = the K-1 largest logits among the collaborator list of the
  *                 slot-0 expert, descending (ties: lower index);
- *   gates[t, s] = softmax over the K kept logits (they sum to 1).
+ *   gates[t, s] = softmax over the K kept logits (they sum to 1), as
+ *                 exp(l - l_slot0) / sum: a token whose largest logit is infinite
+ *                 or a NaN gets NaN gates.
  * collab_idx == NULL selects the conventional top-K of Eq. 1 (used to profile
  * the pre-trained router, Sec. 3.2).
  * x          : [T, d] of x_dt (fp32 or bf16)

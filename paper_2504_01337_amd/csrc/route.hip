@@ -480,9 +480,82 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
             tile[lane * LP + e] = sum[j];
         }
         __syncthreads();
-        if (wave != 0) return;
+        // Selection by all the waves: four lanes per token, each over a quarter of the experts.
+        constexpr int EQ = EP / 4;
+        const int tl = wave * (64 / SEL_WAVES) + (lane >> 2), sub = lane & 3;
+        const int64_t tq = (int64_t)blockIdx.x * 64 + tl;
+        if (tq >= T) return;  // (the four lanes of a token leave together)
+        float lq[EQ];
 #pragma unroll
-        for (int e = 0; e < EP; ++e) l[e] = tile[lane * LP + e];
+        for (int j = 0; j < EQ; ++j) lq[j] = tile[tl * LP + sub * EQ + j];
+        if (logits_out) {
+#pragma unroll
+            for (int j = 0; j < EQ; ++j)
+                if (sub * EQ + j < E) logits_out[(size_t)tq * E + sub * EQ + j] = lq[j];
+        }
+        // The scan "first one standing unless a later one is strictly larger" over all experts,
+        // taken apart: the largest value that is not a NaN (ties to the lower index) of each
+        // quarter, the quarters merged in index order, and at the end the one case in which the
+        // scan differs from that: its first allowed expert holds a NaN, which then stands.
+        auto pick4 = [&](uint64_t m, int &bi, float &bv) __attribute__((always_inline)) {
+            const uint32_t mloc = (uint32_t)(m >> (sub * EQ));
+            bi = -1;
+            bv = 0.0f;
+#pragma unroll
+            for (int j = 0; j < EQ; ++j) {
+                const bool ok = ((mloc >> j) & 1u) != 0;
+                const bool take = ok && (lq[j] > bv || (bi < 0 && lq[j] == lq[j]));
+                bv = take ? lq[j] : bv;
+                bi = take ? sub * EQ + j : bi;
+            }
+#pragma unroll
+            for (int xr = 1; xr <= 2; xr <<= 1) {
+                const int obi = __shfl_xor(bi, xr);
+                const float obv = __shfl_xor(bv, xr);
+                const bool first = (sub & xr) == 0;  // this lane's part holds the lower indices
+                const int abi = first ? bi : obi, bbi = first ? obi : bi;
+                const float abv = first ? bv : obv, bbv = first ? obv : bv;
+                const bool later = abi < 0 || (bbi >= 0 && bbv > abv);
+                bi = later ? bbi : abi;
+                bv = later ? bbv : abv;
+            }
+            if (m != 0) {
+                const int f = __ffsll((unsigned long long)m) - 1;
+                const float lf = tile[tl * LP + f];
+                if (lf != lf) {
+                    bi = f;
+                    bv = lf;
+                }
+            }
+        };
+        int e0;
+        float v0;
+        pick4(all, e0, v0);
+        uint64_t m = mask_tab[e0];
+        const float g0 = expf(v0 - v0);  // 1, or NaN when the largest logit is infinite or a NaN
+        float den = g0;
+        if (sub == 0) {
+            topk_idx[(size_t)tq * K] = e0;
+            gates[(size_t)tq * K] = g0;
+        }
+        for (int s = 1; s < K; ++s) {
+            int e;
+            float v;
+            pick4(m, e, v);
+            float g = 0.0f;
+            if (e >= 0) {
+                m &= ~(1ull << e);
+                g = expf(v - v0);
+            }
+            den += g;
+            if (sub == 0) {
+                topk_idx[(size_t)tq * K + s] = e;
+                gates[(size_t)tq * K + s] = g;
+            }
+        }
+        if (sub == 0)
+            for (int s = 0; s < K; ++s) gates[(size_t)tq * K + s] = gates[(size_t)tq * K + s] / den;
+        return;
     }
     if (t >= T) return;
 
@@ -496,9 +569,10 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
     float v0;
     pick<EP>(l, all, e0, v0);
     uint64_t m = mask_tab[e0];
+    const float g0 = expf(v0 - v0);  // 1, or NaN when the largest logit is infinite or a NaN
     topk_idx[(size_t)t * K] = e0;
-    gates[(size_t)t * K] = 1.0f;
-    float den = 1.0f;
+    gates[(size_t)t * K] = g0;
+    float den = g0;
     for (int s = 1; s < K; ++s) {
         int e;
         float v;

@@ -120,6 +120,33 @@ def test_route_nan_logits_follow_the_stated_rule(c2r, orc):
     assert np.array_equal(host(idx), idx_ref)
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_route_nan_and_inf_logits_through_the_router(c2r, orc, dtype):
+    # infinite router weights meet zero (-> NaN) and non-zero (-> +-inf) activations; one token is all NaN
+    w = wl.scaled(wl.WORKLOADS["C3"], T=300)
+    x = wl.hidden(w).copy()
+    Wg, bias = wl.router(w)
+    Wg = Wg.copy()
+    Wg[5, 0], Wg[7, 9], Wg[300, 59] = np.inf, -np.inf, np.inf
+    x[::3, 5] = 0.0
+    x[1::4, 7] = 0.0
+    x[2::7, 300] = 0.0
+    x[10] = np.nan
+    collab = _collab(w.E, w.Tc, 3)
+    for cl in (collab, None):
+        idx, gates, logits = c2r.route(dev(x, dtype), dev(Wg), dev(bias), w.K,
+                                       None if cl is None else dev(cl), want_logits=True)
+        torch.cuda.synchronize()
+        l_gpu, l_ref = host(logits), orc.logits_canon_f32(x, Wg, bias)
+        assert np.isnan(l_gpu).sum() > 200 and np.isinf(l_gpu).sum() > 200
+        assert np.array_equal(np.isnan(l_gpu), np.isnan(l_ref))
+        ok = ~np.isnan(l_ref)
+        assert np.array_equal(l_gpu[ok].view(np.uint32), l_ref[ok].view(np.uint32))
+        idx_ref, g_ref = orc.route(l_gpu, w.K, cl)
+        assert np.array_equal(host(idx), idx_ref)
+        np.testing.assert_allclose(host(gates), g_ref, rtol=2e-6, atol=1e-7, equal_nan=True)
+
+
 @pytest.mark.parametrize("E,K,T", [(8, 2, 512), (16, 4, 1000), (60, 4, 70001), (64, 6, 129), (33, 3, 64)])
 def test_coactivation(c2r, orc, E, K, T):
     rng = np.random.default_rng(E + T)
