@@ -402,20 +402,19 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
     __shared__ float tile[64 * LP];
 
     const uint64_t all = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
-    if (threadIdx.x < C2R_MAX_E) {
-        const int e = threadIdx.x;
-        uint64_t m = 0;
-        if (e < E) {
-            if (collab_idx) {
-                for (int j = 0; j < Tc; ++j) {
-                    int v = collab_idx[(size_t)e * Tc + j];
-                    if (v >= 0 && v < E && v != e) m |= 1ull << v;
-                }
-            } else {
-                m = all & ~(1ull << e);
-            }
+    // one 64-bit collaborator mask per expert; the list entries are spread over all the threads
+    // (one thread walking a whole list would wait for Tc loads one after another)
+    if (threadIdx.x < C2R_MAX_E)
+        mask_tab[threadIdx.x] = (!collab_idx && (int)threadIdx.x < E) ? all & ~(1ull << threadIdx.x) : 0ull;
+    if (collab_idx) {
+        __syncthreads();
+        const int n = E * Tc;
+#pragma unroll 4
+        for (int i = threadIdx.x; i < n; i += blockDim.x) {
+            const int v = collab_idx[i], e = i / Tc;
+            if (v >= 0 && v < E && v != e)
+                atomicOr(reinterpret_cast<unsigned long long *>(&mask_tab[e]), 1ull << v);
         }
-        mask_tab[e] = m;
     }
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
