@@ -675,12 +675,13 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
         return C2R_ERR_INVALID_ARG;
     }
     const int64_t ntiles = L.Tpad / 64;
-    // Four waves per workgroup share the W sub-tiles.  A batch with fewer than two 64-token
-    // wave tiles per SIMD of the chip uses half-size wave tiles: with one wave per SIMD nothing
-    // hides its latencies (measured at T = 8192, d = 2048, E = 60 on the vector pipe: 54 -> 42 us;
-    // on the matrix pipe the kernel then takes 31 us).
+    // Four waves per workgroup share the W sub-tiles.  On the matrix pipe a wave tile is always
+    // 32 tokens (the pipelined form of the kernel; at E = 60, d = 2048 it beats 64-token tiles
+    // at every batch size: 191 vs 238 us for the stage at T = 65536).  On the vector pipe a batch
+    // with fewer than two 64-token wave tiles per SIMD of the chip uses half-size wave tiles:
+    // with one wave per SIMD nothing hides its latencies.
     const int te = L.EP > 32 ? 8 : L.EP > 16 ? 4 : L.EP > 8 ? 2 : 1;
-    const bool wide = ntiles * L.nchunk >= 2048;
+    const bool wide = ntiles * L.nchunk >= 2048 && te == 1;
     constexpr int NWV = 4;
     const int64_t nwt = wide ? ntiles : ntiles * 2;
     const int64_t nblk = (nwt + NWV - 1) / NWV * L.nchunk;
@@ -697,9 +698,9 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
         default: C2R_ROUTE_LAUNCH(BF, 1, NWV, TQ, false); break;  \
     }
     if (x_dt == C2R_BF16) {
-        if (wide) { C2R_ROUTE_TE(true, NWV, 8) } else { C2R_ROUTE_TE(true, NWV, 4) }
+        if (wide) { C2R_ROUTE_LAUNCH(true, 1, NWV, 8, false); } else { C2R_ROUTE_TE(true, NWV, 4) }
     } else {
-        if (wide) { C2R_ROUTE_TE(false, NWV, 8) } else { C2R_ROUTE_TE(false, NWV, 4) }
+        if (wide) { C2R_ROUTE_LAUNCH(false, 1, NWV, 8, false); } else { C2R_ROUTE_TE(false, NWV, 4) }
     }
 #undef C2R_ROUTE_TE
 #undef C2R_ROUTE_LAUNCH
