@@ -171,6 +171,49 @@ def test_gates_are_softmax_of_kept_logits(orc):
     np.testing.assert_allclose(g, sel / sel.sum(1, keepdims=True), rtol=1e-12)
 
 
+def test_non_finite_logits(orc):
+    # The scan "first allowed expert stands unless a later one is strictly larger", walked here
+    # expert by expert in plain Python: a NaN is selected only where it is the first allowed one.
+    # Gates: the library softmax of the kept logits, which is NaN for a row whose largest kept
+    # logit is +inf or a NaN (inf - inf), and one-hot never.
+    from scipy.special import softmax
+    E, K, Tc = 10, 3, 5
+    l = _small_logits(300, E, 21, ties=True)
+    l[::3, 0] = np.nan
+    l[1::4, 6] = np.nan
+    l[2::5, 3] = np.inf
+    l[5::7, 8] = -np.inf
+    l[11] = np.nan
+    l[12] = -np.inf
+    ci = _random_collab(E, Tc, 22)
+
+    def scan(row, allowed):
+        best = None
+        for e in allowed:
+            if best is None or row[e] > row[best]:
+                best = e
+        return best
+
+    for lists in (ci, None):
+        idx, g = orc.route(l, K, lists)
+        for t in range(l.shape[0]):
+            e0 = scan(l[t], range(E))
+            left = sorted(int(v) for v in (lists[e0] if lists is not None else range(E)) if v != e0)
+            want = [e0]
+            for _ in range(K - 1):
+                e = scan(l[t], left)
+                want.append(e)
+                left.remove(e)
+            assert list(idx[t]) == want, (t, list(idx[t]), want)
+        kept = np.take_along_axis(l.astype(np.float64), idx, axis=1)
+        with np.errstate(invalid="ignore"):
+            ref = softmax(kept, axis=1)
+        assert np.array_equal(np.isnan(g), np.isnan(ref))
+        ok = ~np.isnan(ref)
+        np.testing.assert_allclose(g[ok], ref[ok], rtol=1e-13)
+        assert np.isnan(g[np.isposinf(kept[:, 0])]).all() and np.isnan(g[11]).all() and np.isnan(g[12]).all()
+
+
 # ---------------- Eq. 2 / Eq. 4: profiling ----------------
 
 def test_coactivation_is_MtM(orc):
