@@ -7,9 +7,10 @@
 //    a chain of v_mfma_f32_32x32x2_f32 on the matrix pipe, whose two products per
 //    instruction are added in that same order.  Chunk results go to scratch as
 //    part[tile][chunk][expert][64] (token fastest, one tile's partials contiguous).
-//  route_select_kernel: lane = token.  Adds the chunk results left to right, adds the
-//    bias, then does arg max / masked top-(K-1) entirely in registers with one 64-bit
-//    collaborator mask per expert held in LDS.
+//  route_select_kernel: adds the chunk results left to right (lane = token), adds the
+//    bias, then does arg max / masked top-(K-1) in registers with one 64-bit collaborator
+//    mask per expert held in LDS: four lanes per token over a quarter of the experts each
+//    (chunk partials), or one lane per token over all of them (stored logits).
 #include "c2r_internal.h"
 
 #include <type_traits>
@@ -42,6 +43,9 @@ __global__ __launch_bounds__(256) void pack_router_kernel(const float *__restric
 // identical, denormal and overflow ranges included), so a chain of them over ascending k IS
 // the declared order, at twice the rate the vector pipe reaches without packed instructions.
 // Lanes 0-31 feed k, lanes 32-63 k+1: one W value and one x value per lane and instruction.
+// With 32-token wave tiles a whole chunk is software-pipelined (see PIPE below): operands of
+// sub-tile i in registers, sub-tile i+1 in a ring of three LDS buffers, i+2 on its way from
+// staging registers into LDS, i+3 to i+5 in flight from memory.
 template <bool BF16, int TE, int NWV, int TQ, bool MFMA>
 __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_partial_kernel(const void *__restrict__ x,
                                                                 const float *__restrict__ W, int ldw,
