@@ -218,7 +218,10 @@ def test_permute(c2r, orc, E, K, T, d, dtype, local):
     # tile-map edges: group sizes around the 128-row short-tile and 256-row tile limits, groups of
     # more than one 4-tile chunk, many small groups next to a large one, 64 groups
     ("bf16", 64, 64, [128, 129, 127, 256, 255, 257, 0, 1]), ("bf16", 64, 128, [1100, 3, 0, 0, 2100, 64]),
-    ("bf16", 128, 64, [7] * 30 + [1500] + [0] * 20 + [130] * 13)])
+    ("bf16", 128, 64, [7] * 30 + [1500] + [0] * 20 + [130] * 13),
+    # around the 64-row tile class and the 16-row fragment granularity; then a Zipf-like mix of 48 groups
+    ("bf16", 64, 64, [63, 65, 15, 16, 17, 191, 192, 193, 320, 321, 48, 49]),
+    ("bf16", 64, 128, [int(2600 / (i + 1) ** 1.1) for i in range(48)])])
 def test_expert_ffn_ragged_groups(c2r, orc, dtype, d, F, sizes):
     rng = np.random.default_rng(d + F)
     E = len(sizes)
