@@ -260,10 +260,20 @@ def main():
     fl_dn = 2.0 * n_local * w.d * w.F
     fl_sgu = 4.0 * w.T * w.d * w.F_shared
     fl_sdn = 2.0 * w.T * w.d * w.F_shared
-    for name, fl in (("ffn_gate_up", fl_gu), ("ffn_down", fl_dn), ("shared_gate_up", fl_sgu), ("shared_down", fl_sdn)):
-        if fl > 0:
-            tf = fl / st_ms[name] / 1e9
-            stage_info[name] = {"ms": st_ms[name], "TFLOPs": tf, "frac_mfma": tf / PEAK["mfma_bf16_TFLOPs"]}
+    # a layer that cannot fold the gather into the first pass (or split the shared expert) runs both
+    # passes of that FFN in one call, inside the span of its "gate_up" stage: report them as one
+    both = {"ffn_gate_up": not L.fuse_gather, "shared_gate_up": shared and not L.split_shared}
+    for name, fl, fl2, second in (("ffn_gate_up", fl_gu, fl_dn, "ffn_down"), ("shared_gate_up", fl_sgu, fl_sdn, "shared_down")):
+        if fl <= 0:
+            continue
+        if both[name]:
+            ms = st_ms[name] + st_ms.get(second, 0.0)
+            tf = (fl + fl2) / ms / 1e9
+            stage_info[name.replace("gate_up", "both_passes")] = {"ms": ms, "TFLOPs": tf, "frac_mfma": tf / PEAK["mfma_bf16_TFLOPs"]}
+        else:
+            for nm, f in ((name, fl), (second, fl2)):
+                tf = f / st_ms[nm] / 1e9
+                stage_info[nm] = {"ms": st_ms[nm], "TFLOPs": tf, "frac_mfma": tf / PEAK["mfma_bf16_TFLOPs"]}
     if not L.overlap:
         ffn_span_ms = sum(st_ms.get(k, 0.0) for k in ("ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down"))
     # Group-wise roof of the routed passes: an expert with few rows is bound by streaming its
