@@ -85,9 +85,10 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
     const int64_t t0 = wt * TOK;
     const unsigned char *xb = static_cast<const unsigned char *>(x);
 
-    // global loads of a sub-tile are held in registers until its LDS buffer is free; two sets, so
-    // that a sub-tile is fetched two sub-tiles ahead (on the matrix pipe one sub-tile of compute
-    // is shorter than the memory latency)
+    // global loads of a sub-tile are held in registers until its LDS buffer is free; several sets
+    // (two in the plain loop, three in the pipelined one), so that a sub-tile is fetched two or
+    // three sub-tiles ahead (on the matrix pipe one sub-tile of compute is shorter than the
+    // memory latency)
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
     struct Staged {
