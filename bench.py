@@ -246,13 +246,13 @@ def main():
                            "frac_hbm": route_bytes / st_ms["route"] / 1e6 / PEAK["hbm_GBps"],
                            "frac_valu_f32": route_flops / st_ms["route"] / 1e9 / PEAK["valu_f32_TFLOPs"]}
     perm_bytes = w.T * w.d * sz + n_local * w.d * sz + A * 12
-    stage_info["permute"] = {"ms": st_ms["permute"], "gather_fused_into_gate_up": bool(L.fuse_gather)}
-    if not L.fuse_gather:
+    stage_info["permute"] = {"ms": st_ms["permute"], "gather_fused_into_gate_up": bool(L.fuse_gather or L.gather_both)}
+    if not (L.fuse_gather or L.gather_both):
         stage_info["permute"].update({"GBps": perm_bytes / st_ms["permute"] / 1e6,
                                       "frac_hbm": perm_bytes / st_ms["permute"] / 1e6 / PEAK["hbm_GBps"]})
     stage_info["permute_standalone_with_rows"] = {
         "ms": permute_rows_ms, "GBps": perm_bytes / permute_rows_ms / 1e6,
-        "frac_hbm": perm_bytes / permute_rows_ms / 1e6 / PEAK["hbm_GBps"], "in_step": not L.fuse_gather}
+        "frac_hbm": perm_bytes / permute_rows_ms / 1e6 / PEAK["hbm_GBps"], "in_step": not (L.fuse_gather or L.gather_both)}
     comb_bytes = n_local * w.d * sz + w.T * w.d * sz * (2 if shared else 1) + A * 8
     stage_info["combine"] = {"ms": st_ms["combine"], "GBps": comb_bytes / st_ms["combine"] / 1e6,
                              "frac_hbm": comb_bytes / st_ms["combine"] / 1e6 / PEAK["hbm_GBps"]}

@@ -202,6 +202,20 @@ int c2r_expert_ffn_gate_up_gather(const void *x, c2r_dtype dt, const int32_t *pe
                                   const void *w_gate, const void *w_up, void *h, void *stream);
 
 /*
+ * c2r_expert_ffn (both passes, h in the workspace) with the row gather of the dispatch
+ * (Sec. 3.1) folded into the first pass, as in c2r_expert_ffn_gate_up_gather: x [T, d] is
+ * read through perm and x_perm is never needed.  Unlike the split entry points it takes any
+ * F that c2r_expert_ffn takes (h is padded inside the workspace), e.g. F = 688 or 1376.
+ * Same result as c2r_expert_ffn on the x_perm of c2r_permute, bit for bit.
+ * ws: c2r_workspace_bytes(C2R_STAGE_EXPERT_FFN, A_cap, d, E_local, 1, F, dt) bytes, 256-aligned.
+ * Limits: bf16, d a multiple of 64, T*d*2 < 2^32; otherwise C2R_ERR_UNSUPPORTED.
+ */
+int c2r_expert_ffn_gather(const void *x, c2r_dtype dt, const int32_t *perm, int64_t T, int K,
+                          const int32_t *offsets, int E_local, int64_t A_cap, int d, int F,
+                          const void *w_gate, const void *w_up, const void *w_down, void *y_perm,
+                          void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Un-permute and gate-weighted sum (Sec. 3.1, last sentence):
  *     y[t] = sum_{s<K, inv_perm[t*K+s] >= 0} gates[t,s] * y_perm[inv_perm[t*K+s]]  (+ y_shared[t])
  * summed in fp32 in slot order and rounded once to dt.

@@ -23,7 +23,8 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
 
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
-           "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_down", "c2r_combine",
+           "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_gather", "c2r_expert_ffn_down",
+           "c2r_combine",
            "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies",
            "c2r_collaboration_degree", "c2r_distinct_devices", "c2r_probe_mfma_bf16",
            "c2r_launch_timer_create", "c2r_launch_timer_arm", "c2r_launch_timer_elapsed_ms", "c2r_launch_timer_destroy"]
@@ -59,6 +60,7 @@ def lib():
         L.c2r_expert_ffn.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_expert_ffn_gate_up.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
         L.c2r_expert_ffn_gate_up_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
+        L.c2r_expert_ffn_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_expert_ffn_down.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp]
         L.c2r_combine.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp]
         L.c2r_place_experts.argtypes = [vp, i32, i32, vp, vp]
@@ -228,6 +230,20 @@ def expert_ffn_gate_up_gather(x, perm, K, offsets, w_gate, w_up, h):
     return h
 
 
+def expert_ffn_gather(x, perm, K, offsets, w_gate, w_up, w_down, ws=None, out=None):
+    """Both FFN passes, the first reading row p as x[perm[p] // K]; h lives in the workspace, any F % 8 == 0."""
+    T, d = x.shape
+    A_cap = perm.numel()
+    E_local, F, _ = w_gate.shape
+    assert w_up.shape == (E_local, F, d) and w_down.shape == (E_local, d, F) and perm.dtype == torch.int32
+    y_perm = torch.empty((A_cap, d), dtype=x.dtype, device=x.device) if out is None else out
+    ws = _ws(workspace_bytes(STAGE_EXPERT_FFN, A_cap, d, E_local, 1, F, _dt(x)), x.device, ws)
+    _check("c2r_expert_ffn_gather", lib().c2r_expert_ffn_gather(
+        _ptr(x), _dt(x), _ptr(perm), T, K, _ptr(offsets), E_local, A_cap, d, F, _ptr(w_gate), _ptr(w_up), _ptr(w_down),
+        _ptr(y_perm), _ptr(ws), ws.numel(), _stream()))
+    return y_perm
+
+
 def gather_fusable(dtype, d, F) -> bool:
     """Whether c2r_expert_ffn_gate_up_gather takes this shape (bf16, d and F multiples of 64)."""
     return dtype == torch.bfloat16 and d % 64 == 0 and F % 64 == 0
@@ -386,7 +402,11 @@ class C2RLayer:
         # fold the dispatch's row gather into the first FFN pass when the shape allows it:
         # x_perm is then never written
         self.fuse_gather = gather_fusable(dtype, d, F) if fuse_gather is None else fuse_gather
-        self.x_perm = None if self.fuse_gather else torch.empty((T * K, d), dtype=dtype, device=dev)
+        # ... or, when only F stands in the way (h needs a padded pitch), into c2r_expert_ffn_gather,
+        # which runs both passes out of its workspace
+        self.gather_both = (fuse_gather is None and not self.fuse_gather and dtype == torch.bfloat16
+                            and d % 64 == 0 and T * d * 2 < (1 << 32))
+        self.x_perm = None if self.fuse_gather or self.gather_both else torch.empty((T * K, d), dtype=dtype, device=dev)
         # the two FFN passes are enqueued as calls of their own when h needs no padded pitch
         # (then the layer owns h); otherwise c2r_expert_ffn runs both out of its workspace
         self.h = torch.empty((T * K, F), dtype=dtype, device=dev) if self.fuse_gather else None
@@ -441,6 +461,8 @@ class C2RLayer:
         def gate_up():
             if self.fuse_gather:
                 expert_ffn_gate_up_gather(x, self.perm, self.K, self.offsets, self.w[0], self.w[1], self.h)
+            elif self.gather_both:   # both passes, rows read through perm
+                expert_ffn_gather(x, self.perm, self.K, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
             else:   # both passes
                 expert_ffn(self.x_perm, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
 

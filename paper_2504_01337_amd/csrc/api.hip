@@ -145,6 +145,29 @@ extern "C" int c2r_expert_ffn(const void *x_perm, c2r_dtype dt, const int32_t *o
     return ffn_pass(1, dt, ws, offsets, E_local, A_cap, d, F, ldh, w_down, nullptr, y_perm, stream);
 }
 
+extern "C" int c2r_expert_ffn_gather(const void *x, c2r_dtype dt, const int32_t *perm, int64_t T, int K,
+                                     const int32_t *offsets, int E_local, int64_t A_cap, int d, int F,
+                                     const void *w_gate, const void *w_up, const void *w_down, void *y_perm,
+                                     void *ws, size_t ws_bytes, void *stream) {
+    int rc = check_ffn(dt, E_local, A_cap, d, F);
+    if (rc != C2R_OK) return rc;
+    if (T < 1 || K < 1) return C2R_ERR_INVALID_ARG;
+    if (A_cap == 0) return C2R_OK;
+    if (!x || !perm || !offsets || !w_gate || !w_up || !w_down || !y_perm) return C2R_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(w_down, 16) || !aligned(y_perm, 16))
+        return C2R_ERR_INVALID_ARG;
+    // only the copy-engine kernel folds the gather into its addresses (32-bit row offsets into x)
+    if (!fast_bf16(dt, d, F) || (uint64_t)T * d * 2 >= (1ull << 32)) return C2R_ERR_UNSUPPORTED;
+    const int ldh = h_pitch(dt, d, F);
+    const size_t need = round_up((size_t)A_cap * ldh * 2, 256);
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return C2R_ERR_WORKSPACE;
+    rc = launch_ffn_bf16_dma_pass(0, static_cast<const uint16_t *>(x), d, offsets, E_local, A_cap, d, F,
+                                  static_cast<const uint16_t *>(w_gate), static_cast<const uint16_t *>(w_up),
+                                  static_cast<uint16_t *>(ws), ldh, perm, K, (int)T, static_cast<hipStream_t>(stream));
+    if (rc != C2R_OK) return rc;
+    return ffn_pass(1, dt, ws, offsets, E_local, A_cap, d, F, ldh, w_down, nullptr, y_perm, stream);
+}
+
 // ---- measurement aid: the duration of one launch, taken from the dispatch itself ----
 namespace c2r {
 thread_local LaunchTimer *armed_launch_timer = nullptr;

@@ -65,6 +65,10 @@ def test_argument_errors_before_launch():
     assert L.c2r_combine(null, 1, p, p, 16, 64, 2, null, p, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_expert_ffn_gate_up_gather(p, 0, p, 16, 2, p, 4, 32, 64, 64, p, p, p, null) == c2r.ERR_UNSUPPORTED  # fp32
     assert L.c2r_expert_ffn_gate_up_gather(p, 1, null, 16, 2, p, 4, 32, 64, 64, p, p, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_expert_ffn_gather(p, 0, p, 16, 2, p, 4, 32, 64, 64, p, p, p, p, p, 1 << 20, null) == c2r.ERR_UNSUPPORTED  # fp32
+    assert L.c2r_expert_ffn_gather(p, 1, p, 16, 2, p, 4, 32, 72, 64, p, p, p, p, p, 1 << 20, null) == c2r.ERR_UNSUPPORTED  # d % 64
+    assert L.c2r_expert_ffn_gather(p, 1, null, 16, 2, p, 4, 32, 64, 88, p, p, p, p, p, 1 << 20, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_expert_ffn_gather(p, 1, p, 16, 2, p, 4, 32, 64, 88, p, p, p, p, null, 0, null) == c2r.ERR_WORKSPACE
     assert L.c2r_place_experts(p, 65, 4, p, null) == c2r.ERR_UNSUPPORTED
     assert L.c2r_place_experts(null, 8, 4, p, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_place_experts(p, 8, 0, p, null) == c2r.ERR_INVALID_ARG

@@ -41,7 +41,7 @@ def _run_layer(c2r, orc, w, n_sample):
     y = layer.forward(x)
     y = layer.forward(x)            # twice: buffers are reused, the result must not depend on it
     torch.cuda.synchronize()
-    if layer.fuse_gather:
+    if layer.fuse_gather or layer.gather_both:
         # the same layer through c2r_permute's x_perm and c2r_expert_ffn, and with the shared
         # expert (if any) on a second stream: identical bits
         plain = c2r.C2RLayer(w.T, w.d, w.E, w.K, w.F, tdt, Wg, bias, collab, *layer.w,

@@ -272,6 +272,32 @@ def test_gate_up_gather_equals_gate_up_on_x_perm(c2r, E, K, T, d, F, local):
     assert n > 0 and torch.all(h1[n:] == 7.0)
 
 
+@pytest.mark.parametrize("E,K,T,d,F,local", [(16, 4, 600, 256, 688, None), (8, 2, 513, 128, 1376, None),
+                                              (12, 3, 300, 64, 88, 5), (8, 2, 700, 128, 256, None)])
+def test_ffn_gather_equals_ffn_on_x_perm(c2r, E, K, T, d, F, local):
+    """Both passes with the gather folded in, for any F the library takes (h padded inside the
+    workspace): bit for bit what c2r_expert_ffn gives on the x_perm of c2r_permute."""
+    rng = np.random.default_rng(E + T + F)
+    idx = np.stack([rng.permutation(E)[:K] for _ in range(T)]).astype(np.int32)
+    x = dev(wl.round_bf16(rng.standard_normal((T, d)).astype(np.float32)), "bf16")
+    ls, E_local = None, E
+    if local:
+        ls = np.full(E, -1, dtype=np.int32)
+        ls[np.sort(rng.permutation(E)[:local])] = rng.permutation(local).astype(np.int32)
+        E_local = local
+    counts, offsets, perm, inv, x_perm = c2r.permute(x, dev(idx), E, dev(ls), E_local)
+    w = [dev(wl.round_bf16((rng.standard_normal(shape) * 0.05).astype(np.float32)), "bf16")
+         for shape in ((E_local, F, d), (E_local, F, d), (E_local, d, F))]
+    y0 = torch.full((T * K, d), 7.0, dtype=torch.bfloat16, device="cuda")
+    y1 = y0.clone()
+    c2r.expert_ffn(x_perm, offsets, *w, out=y0)
+    c2r.expert_ffn_gather(x, perm, K, offsets, *w, out=y1)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    n = int(offsets[-1])
+    assert n > 0 and torch.all(y1[n:] == 7.0) and not torch.all(y1[:n] == 7.0)
+
+
 def test_gate_up_gather_rejects_other_shapes(c2r):
     x = torch.zeros((8, 72), dtype=torch.float32, device="cuda")
     perm = torch.zeros((8,), dtype=torch.int32, device="cuda")
