@@ -11,7 +11,9 @@
 //  4. permute_rows_kernel   one wave per token: the row of x is read once and
 //                           written to each of its (up to K) sorted positions
 //                           with 16-byte accesses
-// Up to 2^18 assignments, steps 1-3 are one launch instead (permute_by_slot_kernel).
+// Up to 49152 assignments, steps 1-3 are one launch instead (permute_by_slot_kernel: 11 us at
+// 32768 assignments and linear in their number; the three launches take 16-24 us from 65536 to
+// 262144 assignments).
 // Everything is deterministic: no atomically assigned slots.
 #include "c2r_internal.h"
 
@@ -48,16 +50,34 @@ __global__ __launch_bounds__(PB_THREADS) void permute_hist_kernel(
     if (threadIdx.x < E_local) block_counts[(size_t)blockIdx.x * E_local + threadIdx.x] = hist[threadIdx.x];
 }
 
-// One block of 64 threads; thread s walks the blocks for slot s.
-__global__ __launch_bounds__(64) void permute_scan_kernel(const int32_t *__restrict__ block_counts,
-                                                          int nblocks, int E_local,
-                                                          int32_t *__restrict__ block_base,
-                                                          int32_t *__restrict__ counts,
-                                                          int32_t *__restrict__ offsets) {
-    const int s = threadIdx.x;
-    int32_t total = 0;
-    if (s < E_local)
-        for (int b = 0; b < nblocks; ++b) total += block_counts[(size_t)b * E_local + s];
+// One workgroup of SCAN_WAVES waves; lane s works for slot s, wave w for a contiguous share of
+// the blocks (loads of a share are independent of one another, so they are in flight together;
+// one thread walking all the blocks of a large batch would wait for them one by one).
+constexpr int SCAN_WAVES = 16;
+
+__global__ __launch_bounds__(SCAN_WAVES * 64) void permute_scan_kernel(const int32_t *__restrict__ block_counts,
+                                                                      int nblocks, int E_local,
+                                                                      int32_t *__restrict__ block_base,
+                                                                      int32_t *__restrict__ counts,
+                                                                      int32_t *__restrict__ offsets) {
+    __shared__ int32_t share_total[SCAN_WAVES][64];
+    const int s = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int per = (nblocks + SCAN_WAVES - 1) / SCAN_WAVES;
+    const int b0 = min(w * per, nblocks), b1 = min(b0 + per, nblocks);
+    int32_t mine = 0;
+    if (s < E_local) {
+#pragma unroll 8
+        for (int b = b0; b < b1; ++b) mine += block_counts[(size_t)b * E_local + s];
+    }
+    share_total[w][s] = mine;
+    __syncthreads();
+    int32_t total = 0, before = 0;  // the slot's count; its count in the shares of lower waves
+#pragma unroll
+    for (int v = 0; v < SCAN_WAVES; ++v) {
+        const int32_t t = share_total[v][s];
+        before += v < w ? t : 0;
+        total += t;
+    }
     // exclusive scan over slots (64 lanes)
     int32_t incl = total;
 #pragma unroll
@@ -67,11 +87,14 @@ __global__ __launch_bounds__(64) void permute_scan_kernel(const int32_t *__restr
     }
     const int32_t excl = incl - total;
     if (s < E_local) {
-        counts[s] = total;
-        offsets[s] = excl;
-        if (s == E_local - 1) offsets[E_local] = incl;
-        int32_t run = excl;
-        for (int b = 0; b < nblocks; ++b) {
+        if (w == 0) {
+            counts[s] = total;
+            offsets[s] = excl;
+            if (s == E_local - 1) offsets[E_local] = incl;
+        }
+        int32_t run = excl + before;
+#pragma unroll 8
+        for (int b = b0; b < b1; ++b) {
             block_base[(size_t)b * E_local + s] = run;
             run += block_counts[(size_t)b * E_local + s];
         }
@@ -146,6 +169,7 @@ __global__ __launch_bounds__(PB_THREADS) void permute_rank_kernel(
 // waves), which is the same stable order as the counting sort above.  Workgroup 0 also
 // marks the assignments that belong to no local slot.
 constexpr int PE_WAVES = 16;
+constexpr int64_t BY_SLOT_MAX = 3 << 14;  // assignments up to which the one-launch form is the faster one
 constexpr int PE_STEPS = 32;  // 64-assignment steps a wave holds in registers at a time
 
 __global__ __launch_bounds__(PE_WAVES * 64) void permute_by_slot_kernel(
@@ -303,7 +327,7 @@ extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx,
     if (nblocks > 0 && (!ws || ws_bytes < 2 * half || !aligned(ws, 256))) return C2R_ERR_WORKSPACE;
     int32_t *block_counts = static_cast<int32_t *>(ws);
     int32_t *block_base = reinterpret_cast<int32_t *>(static_cast<char *>(ws) + half);
-    if (A > 0 && A <= (1 << 18)) {
+    if (A > 0 && A <= BY_SLOT_MAX) {
         // the index array is swept once per slot out of L2, in one launch
         permute_by_slot_kernel<<<dim3((unsigned)E_local), dim3(PE_WAVES * 64), 0, st>>>(
             topk_idx, (int)A, E, local_slot, E_local, counts, offsets, perm, inv_perm);
@@ -311,8 +335,8 @@ extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx,
         if (nblocks > 0)
             permute_hist_kernel<<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
                 topk_idx, A, E, local_slot, E_local, block_counts);
-        permute_scan_kernel<<<dim3(1), dim3(64), 0, st>>>(block_counts, (int)nblocks, E_local, block_base, counts,
-                                                          offsets);
+        permute_scan_kernel<<<dim3(1), dim3(SCAN_WAVES * 64), 0, st>>>(block_counts, (int)nblocks, E_local,
+                                                                      block_base, counts, offsets);
         if (nblocks > 0)
             permute_rank_kernel<<<dim3((unsigned)nblocks), dim3(PB_THREADS), 0, st>>>(
                 topk_idx, A, E, local_slot, E_local, block_base, perm, inv_perm);

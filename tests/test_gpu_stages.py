@@ -185,9 +185,10 @@ def test_collaborators(c2r, orc, E):
 @pytest.mark.parametrize("E,K,T,d,dtype,local", [
     (8, 2, 512, 256, "f32", None), (60, 4, 3001, 64, "bf16", None), (60, 4, 5000, 128, "bf16", 15),
     (16, 4, 1, 64, "bf16", None), (64, 1, 1025, 72, "f32", 7), (5, 5, 300, 8, "f32", None),
-    # more than 2^18 assignments: the histogram / scan / rank launches instead of the one-launch sweep;
-    # exactly 2^18 and 2^18 + 4: either side of the switch
-    (60, 4, 70001, 8, "bf16", None), (16, 4, 65536, 8, "bf16", 5), (16, 4, 65537, 8, "bf16", None)])
+    # more than 49152 assignments: the histogram / scan / rank launches instead of the one-launch sweep;
+    # 49152 and 49153: either side of the switch; 2^15 + 1: the one-launch sweep's second register pass
+    (60, 4, 70001, 8, "bf16", None), (16, 4, 65536, 8, "bf16", 5), (16, 4, 65537, 8, "bf16", None),
+    (60, 3, 16384, 8, "bf16", None), (16, 1, 49153, 8, "bf16", 5), (33, 1, 32769, 8, "bf16", None)])
 def test_permute(c2r, orc, E, K, T, d, dtype, local):
     rng = np.random.default_rng(E * 7 + T)
     logits = rng.standard_normal((T, E)).astype(np.float32)
