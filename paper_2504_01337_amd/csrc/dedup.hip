@@ -25,28 +25,62 @@ __device__ __forceinline__ int device_of(int e, int E, const int32_t *__restrict
     return (g >= 0 && g < n_dev) ? g : -1;
 }
 
+// The expert -> device map of the call, checked once per workgroup into LDS (-1: no device).
+__device__ __forceinline__ void load_device_table(int32_t *tab, int E, const int32_t *__restrict__ expert_device,
+                                                  int n_dev) {
+    if (threadIdx.x < C2R_MAX_E) {
+        const int e = threadIdx.x;
+        tab[e] = e < E ? device_of(e, E, expert_device, n_dev) : -1;
+    }
+    __syncthreads();
+}
+
+// Devices of a token's K experts.  The K indices are loaded together (independent loads); for
+// K <= 8 the devices are also returned packed, one byte per slot (device + 1, 0: none), so that
+// the caller need not load the indices again.
 __device__ __forceinline__ uint64_t device_set(const int32_t *__restrict__ topk_idx, int64_t t, int64_t T, int K,
-                                               int E, const int32_t *__restrict__ expert_device, int n_dev) {
-    uint64_t m = 0;
-    if (t < T)
-        for (int s = 0; s < K; ++s) {
-            const int g = device_of(topk_idx[t * K + s], E, expert_device, n_dev);
-            if (g >= 0) m |= 1ull << g;
+                                               int E, const int32_t *tab, uint64_t *packed = nullptr) {
+    uint64_t m = 0, pk = 0;
+    if (t < T) {
+        if (K <= 8) {
+            int32_t e[8];
+#pragma unroll
+            for (int s = 0; s < 8; ++s) e[s] = topk_idx[t * K + (s < K ? s : K - 1)];  // (no load behind a branch)
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const int g = (s < K && e[s] >= 0 && e[s] < E) ? tab[e[s]] : -1;
+                if (g >= 0) {
+                    m |= 1ull << g;
+                    pk |= (uint64_t)(g + 1) << (8 * s);
+                }
+            }
+        } else {
+            for (int s = 0; s < K; ++s) {
+                const int32_t e = topk_idx[t * K + s];
+                const int g = (e >= 0 && e < E) ? tab[e] : -1;
+                if (g >= 0) m |= 1ull << g;
+            }
         }
+    }
+    if (packed) *packed = pk;
     return m;
 }
 
 __global__ __launch_bounds__(DB_THREADS) void dedup_count_kernel(
     const int32_t *__restrict__ topk_idx, int64_t T, int K, int E, const int32_t *__restrict__ expert_device,
     int n_dev, int32_t *__restrict__ block_counts) {
-    __shared__ int32_t hist[C2R_MAX_E];
+    __shared__ int32_t hist[C2R_MAX_E], dev_tab[C2R_MAX_E];
     if (threadIdx.x < C2R_MAX_E) hist[threadIdx.x] = 0;
-    __syncthreads();
+    load_device_table(dev_tab, E, expert_device, n_dev);
     const int lane = threadIdx.x & 63;
     const int64_t base = (int64_t)blockIdx.x * DB_SPAN;
+    uint64_t sets[DB_ITEMS];
+#pragma unroll
+    for (int i = 0; i < DB_ITEMS; ++i)
+        sets[i] = device_set(topk_idx, base + i * DB_THREADS + threadIdx.x, T, K, E, dev_tab);
 #pragma unroll
     for (int i = 0; i < DB_ITEMS; ++i) {
-        const uint64_t m = device_set(topk_idx, base + i * DB_THREADS + threadIdx.x, T, K, E, expert_device, n_dev);
+        const uint64_t m = sets[i];
         for (int g = 0; g < n_dev; ++g) {
             const int c = __popcll(__ballot((m >> g) & 1ull));
             if (lane == 0 && c) atomicAdd(&hist[g], c);
@@ -64,11 +98,13 @@ __global__ __launch_bounds__(DB_THREADS) void dedup_rank_kernel(
     int32_t *__restrict__ send_offsets, int32_t *__restrict__ send_token, int32_t *__restrict__ send_row) {
     __shared__ int32_t step_cnt[DB_STEPS][C2R_MAX_E];
     __shared__ int32_t part_tot[DB_THREADS / 64][C2R_MAX_E], part_pre[DB_THREADS / 64][C2R_MAX_E];
-    __shared__ int32_t run_base[C2R_MAX_E];
+    __shared__ int32_t run_base[C2R_MAX_E], dev_tab[C2R_MAX_E];
+    load_device_table(dev_tab, E, expert_device, n_dev);
     {
         const int g = threadIdx.x & 63, part = threadIdx.x >> 6;
         int32_t tot = 0, pre = 0;
         if (g < n_dev)
+#pragma unroll 8
             for (int b = part; b < nblocks; b += DB_THREADS / 64) {
                 const int32_t v = block_counts[(size_t)b * n_dev + g];
                 tot += v;
@@ -101,11 +137,13 @@ __global__ __launch_bounds__(DB_THREADS) void dedup_rank_kernel(
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t base = (int64_t)blockIdx.x * DB_SPAN;
     const uint64_t lt = lane == 0 ? 0ull : (~0ull >> (64 - lane));
-    uint64_t sets[DB_ITEMS];
+    uint64_t sets[DB_ITEMS], packed[DB_ITEMS];
+#pragma unroll
+    for (int i = 0; i < DB_ITEMS; ++i)
+        sets[i] = device_set(topk_idx, base + i * DB_THREADS + threadIdx.x, T, K, E, dev_tab, &packed[i]);
 #pragma unroll
     for (int i = 0; i < DB_ITEMS; ++i) {
         const int q = i * (DB_THREADS / 64) + wave;  // wave step q covers 64 consecutive tokens
-        sets[i] = device_set(topk_idx, base + i * DB_THREADS + threadIdx.x, T, K, E, expert_device, n_dev);
         for (int g = 0; g < n_dev; ++g) {
             const int c = __popcll(__ballot((sets[i] >> g) & 1ull));
             if (lane == 0) step_cnt[q][g] = c;
@@ -133,13 +171,30 @@ __global__ __launch_bounds__(DB_THREADS) void dedup_rank_kernel(
             if (mine) {
                 const int32_t pos = step_cnt[q][g] + __popcll(bal & lt);
                 send_token[pos] = (int32_t)t;
-                for (int s = 0; s < K; ++s)
-                    if (device_of(topk_idx[t * K + s], E, expert_device, n_dev) == g) send_row[t * K + s] = pos;
+                if (K <= 8) {
+#pragma unroll
+                    for (int s = 0; s < 8; ++s)
+                        if (s < K && (int)((packed[i] >> (8 * s)) & 0xff) == g + 1) send_row[t * K + s] = pos;
+                } else {
+                    for (int s = 0; s < K; ++s) {
+                        const int32_t e = topk_idx[t * K + s];
+                        if (e >= 0 && e < E && dev_tab[e] == g) send_row[t * K + s] = pos;
+                    }
+                }
             }
         }
-        if (t < T)
-            for (int s = 0; s < K; ++s)
-                if (device_of(topk_idx[t * K + s], E, expert_device, n_dev) < 0) send_row[t * K + s] = -1;
+        if (t < T) {
+            if (K <= 8) {
+#pragma unroll
+                for (int s = 0; s < 8; ++s)
+                    if (s < K && ((packed[i] >> (8 * s)) & 0xff) == 0) send_row[t * K + s] = -1;
+            } else {
+                for (int s = 0; s < K; ++s) {
+                    const int32_t e = topk_idx[t * K + s];
+                    if (!(e >= 0 && e < E && dev_tab[e] >= 0)) send_row[t * K + s] = -1;
+                }
+            }
+        }
     }
 }
 
