@@ -102,7 +102,8 @@ __global__ __launch_bounds__(64) void collaborators_kernel(const int32_t *__rest
 // are filled in order with ceil(E / n_dev) experts each: a device starts with the unplaced
 // expert whose row of C (diagonal left out) sums highest and then keeps taking the unplaced
 // expert with the largest total co-activation with its members; ties go to the lower index.
-// The row of C sits in LDS; each step is a masked row sum per lane and a wave-wide arg max.
+// C sits in LDS; each step adds the new member's column entry to a running sum per lane and takes
+// a wave-wide arg max.
 __global__ __launch_bounds__(64) void place_experts_kernel(const int32_t *__restrict__ C, int E, int n_dev,
                                                            int32_t *__restrict__ expert_device) {
     __shared__ int32_t Cl[C2R_MAX_E][C2R_MAX_E + 1];
@@ -112,14 +113,16 @@ __global__ __launch_bounds__(64) void place_experts_kernel(const int32_t *__rest
     const int cap = (E + n_dev - 1) / n_dev;
     uint64_t placed = 0;  // wave-uniform
     int mine = -1;
+    long long row_sum = 0;  // this expert's row of C without the diagonal: its score for an empty device
+    if (e < E)
+        for (int j = 0; j < E; ++j)
+            if (j != e) row_sum += Cl[e][j];
     for (int g = 0; g < n_dev; ++g) {
         uint64_t members = 0;
+        long long with_members = 0;  // co-activation with the device's members, kept up as they join
         for (int m = 0; m < cap; ++m) {
             const bool free_lane = e < E && !((placed >> e) & 1ull);
-            long long score = 0;
-            if (free_lane)
-                for (int j = 0; j < E; ++j)
-                    if (j != e && (members == 0 || ((members >> j) & 1ull))) score += Cl[e][j];
+            const long long score = members == 0 ? row_sum : with_members;
             // arg max over the free lanes, lower index on ties: the largest score first ...
             long long best = free_lane ? score : -1;  // scores are sums of counts, never negative
 #pragma unroll
@@ -133,6 +136,7 @@ __global__ __launch_bounds__(64) void place_experts_kernel(const int32_t *__rest
             if (e == pick) mine = g;
             placed |= 1ull << pick;
             members |= 1ull << pick;
+            if (e < E && e != pick) with_members += Cl[e][pick];
         }
     }
     if (e < E) expert_device[e] = mine;
