@@ -349,7 +349,9 @@ def test_probe_mfma_counts_its_work(c2r):
 
 
 @pytest.mark.parametrize("E,K,T,n_dev,holes", [(12, 4, 300, 4, True), (60, 4, 5000, 4, False), (64, 8, 1025, 64, True),
-                                               (8, 2, 1, 2, False), (60, 4, 8192, 6, False), (16, 1, 4100, 3, True)])
+                                               (8, 2, 1, 2, False), (60, 4, 8192, 6, False), (16, 1, 4100, 3, True),
+                                               # K > 8: the devices of a token no longer fit one packed register
+                                               (24, 9, 700, 5, True), (64, 16, 1030, 8, False)])
 def test_dedup_dispatch(c2r, orc, E, K, T, n_dev, holes):
     """Sec. 3.4: send list (device-major, tokens ascending) and copy row per assignment, bit exact."""
     rng = np.random.default_rng(E * 13 + T)
