@@ -456,32 +456,44 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
         for (int e = 0; e < EP; ++e) l[e] = (e < E && lane < rows) ? tl[lane * LP + e] : 0.0f;
     } else {
         static_assert(EP % SEL_WAVES == 0, "experts divide over the waves");
-        constexpr int EW = EP / SEL_WAVES;
-        const float *p = src + (size_t)blockIdx.x * nchunk * EP * 64 + (size_t)wave * EW * 64 + lane;
-        // chunk results are added left to right; four chunks are fetched at a time so that
-        // their loads are in flight together
-        constexpr int CU = 4;
-        float sum[EW];
+        constexpr int EW = EP / SEL_WAVES;   // experts of this wave
+        constexpr int ES = (EW + 3) / 4;     // in steps of four
+        // A lane adds up four tokens (16-byte loads) of one expert per step: lane = (token quad,
+        // expert within the step).  Chunk results are added left to right; eight chunks x ES
+        // loads are in flight together (the partial sums were written by other XCDs a moment
+        // ago, so every batch costs a trip to memory), all of them unconditional on clamped
+        // indices.
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        constexpr int CU = 8;
+        const int tq4 = lane & 15, es = lane >> 4;
+        const float *p = src + ((size_t)blockIdx.x * nchunk * EP + (size_t)wave * EW) * 64 + 4 * tq4;
+        f32x4 sum[ES];
         for (int c0 = 0; c0 < nchunk; c0 += CU) {
-            float v[CU][EW];
+            f32x4 v[CU][ES];
 #pragma unroll
-            for (int u = 0; u < CU; ++u)
-                if (c0 + u < nchunk) {
+            for (int u = 0; u < CU; ++u) {
+                const int cc = min(c0 + u, nchunk - 1);
 #pragma unroll
-                    for (int j = 0; j < EW; ++j) v[u][j] = p[(size_t)(c0 + u) * EP * 64 + j * 64];
+                for (int j = 0; j < ES; ++j) {
+                    const int el = min(4 * j + es, EW - 1);
+                    v[u][j] = *reinterpret_cast<const f32x4 *>(p + ((size_t)cc * EP + el) * 64);
                 }
+            }
 #pragma unroll
-            for (int u = 0; u < CU; ++u)
-                if (c0 + u < nchunk) {
+            for (int u = 0; u < CU; ++u) {
+                const bool have = c0 + u < nchunk;  // wave-uniform
 #pragma unroll
-                    for (int j = 0; j < EW; ++j) sum[j] = (c0 + u == 0) ? v[u][j] : sum[j] + v[u][j];
-                }
+                for (int j = 0; j < ES; ++j) sum[j] = !have ? sum[j] : (c0 + u == 0) ? v[u][j] : sum[j] + v[u][j];
+            }
         }
 #pragma unroll
-        for (int j = 0; j < EW; ++j) {
-            const int e = wave * EW + j;
-            if (bias && e < E) sum[j] = sum[j] + bias[e];
-            tile[lane * LP + e] = sum[j];
+        for (int j = 0; j < ES; ++j) {
+            const int el = 4 * j + es, e = wave * EW + el;
+            if (el < EW) {
+                if (bias && e < E) sum[j] = sum[j] + bias[e];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) tile[(4 * tq4 + i) * LP + e] = sum[j][i];
+            }
         }
         __syncthreads();
         // Selection by all the waves: four lanes per token, each over a quarter of the experts.
