@@ -7,7 +7,7 @@
 //    a chain of v_mfma_f32_32x32x2_f32 on the matrix pipe, whose two products per
 //    instruction are added in that same order.  Chunk results go to scratch as
 //    part[tile][chunk][expert][64] (token fastest, one tile's partials contiguous).
-//  route_select_kernel: adds the chunk results left to right (lane = token), adds the
+//  route_select_kernel: adds the chunk results left to right (four tokens per lane), adds the
 //    bias, then does arg max / masked top-(K-1) in registers with one 64-bit collaborator
 //    mask per expert held in LDS: four lanes per token over a quarter of the experts each
 //    (chunk partials), or one lane per token over all of them (stored logits).
