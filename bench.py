@@ -21,6 +21,224 @@ if ROOT not in sys.path:
 PEAK = {"hbm_GBps": 8000.0, "mfma_bf16_TFLOPs": 2500.0, "valu_f32_TFLOPs": 157.3}
 
 
+def _benchaid():
+    """The benchmark's own probe library (not part of the C2R ABI): a pure bf16 MFMA loop."""
+    import ctypes as C
+    path = os.path.join(ROOT, "paper_2504_01337_amd", "bench_aids", "libc2r_benchaid.so")
+    if not os.path.exists(path):
+        return None
+    L = C.CDLL(path)
+    L.benchaid_probe_mfma_bf16.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.POINTER(C.c_double),
+                                           C.c_void_p, C.c_void_p]
+    L.benchaid_probe_mfma_bf16.restype = C.c_int
+    return L
+
+
+def measured_ceilings(torch):
+    """Ceilings of this box: the matrix pipe on zero / random operands (with the shader clock the
+    loop ran at) and a plain device copy."""
+    import ctypes as C
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    res = {}
+    aid = _benchaid()
+    if aid is not None:
+        out_p = torch.empty(1024 * 512, dtype=torch.float32, device="cuda")
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        g = torch.Generator(device="cpu").manual_seed(7)
+
+        def probe(ops, iters, clk):
+            fl = C.c_double(0.0)
+            rc = aid.benchaid_probe_mfma_bf16(C.c_void_p(ops.data_ptr()), iters, 1024, C.c_void_p(out_p.data_ptr()),
+                                              C.byref(fl), C.c_void_p(clk.data_ptr()) if clk is not None else None, st)
+            assert rc == 0, rc
+            return fl.value
+
+        for name, ops in (("mfma_bf16_zero_operands_TFLOPs", torch.zeros(1024 * 8, dtype=torch.bfloat16)),
+                          ("mfma_bf16_random_operands_TFLOPs",
+                           (torch.rand(1024 * 8, generator=g) * 2 - 1).to(torch.bfloat16))):
+            ops = ops.cuda()
+            clk = torch.zeros(2, dtype=torch.int64, device="cuda")
+            probe(ops, 2000, None)
+            e0.record()
+            fl = probe(ops, 20000, clk)
+            e1.record()
+            torch.cuda.synchronize()
+            res[name] = fl / e0.elapsed_time(e1) / 1e9
+            cyc, ticks = clk.tolist()   # shader cycles / 100 MHz ticks of the loop: the clock under this load
+            res[name.replace("_TFLOPs", "_shader_clock_GHz")] = cyc / (ticks / 1e8) / 1e9 if ticks else None
+    src = torch.full(((512 << 20) // 4,), 1.0, dtype=torch.float32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    e0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    res["copy_read_plus_write_GBps"] = 5 * 2 * (512 << 20) / e0.elapsed_time(e1) / 1e6
+    return res
+
+
+class ColdTimer:
+    """Times one launch from cold memory.  Two protocols, because they differ by a factor of two on
+    this chip: "after_write" = a 512 MiB fill before the launch (the memory-side cache is then full
+    of dirty lines whose write-back competes with the launch's own traffic: even a plain device copy
+    runs at 3.7 instead of 5.4 TB/s behind it); "after_read" = that fill followed by a 1 GiB read
+    (the caches then hold clean lines of an unrelated buffer).  A plain device-to-device copy is
+    timed the same way as the yardstick of each protocol."""
+
+    def __init__(self, torch):
+        self.torch = torch
+        self.w = torch.empty((512 << 20) // 4, dtype=torch.float32, device="cuda")
+        self.r = torch.ones((1024 << 20) // 4, dtype=torch.float32, device="cuda")
+        self.cs = torch.ones((96 << 20) // 4, dtype=torch.float32, device="cuda")
+        self.cd = torch.empty_like(self.cs)
+
+    def flush(self, mode):
+        self.w.fill_(1.0)
+        if mode == "after_read":
+            self.r.sum()
+
+    def time(self, prepare, launch, n_it, mode):
+        """median microseconds of launch() behind prepare() (re-creates the launch's inputs) + flush"""
+        torch = self.torch
+        ts = []
+        for _ in range(n_it):
+            prepare()
+            self.flush(mode)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            launch()
+            b.record()
+            torch.cuda.synchronize()
+            ts.append(a.elapsed_time(b) * 1e3)
+        ts.sort()
+        return ts[len(ts) // 2]
+
+    def copy_yardstick(self, n_it):
+        out = {}
+        for mode in ("after_write", "after_read"):
+            us = self.time(lambda: None, lambda: self.cd.copy_(self.cs), n_it, mode)
+            out[mode] = {"us": us, "GBps": 2 * self.cs.numel() * 4 / us / 1e3}
+        return out
+
+
+def bench_profiling(args, w, torch, np, c2r, wl):
+    """Workload C4: the offline profiling of Sec. 3.2 / Sec. 3.3 step 1 on a stored logit stream.
+    A step = conventional top-K of every token (c2r_route_from_logits) -> co-activation matrix
+    (Eq. 2, c2r_build_coactivation into a zeroed C) -> collaborator lists (Eq. 4, c2r_collaborators)."""
+    t_gen = time.time()
+    lg_h = wl.direct_logits(w)
+    lg = torch.from_numpy(lg_h).cuda()
+    T, E, K, Tc = w.T, w.E, w.K, w.Tc
+    idx = torch.empty((T, K), dtype=torch.int32, device="cuda")
+    gates = torch.empty((T, K), dtype=torch.float32, device="cuda")
+    Cm = torch.zeros((E, E), dtype=torch.int32, device="cuda")
+    lists = (torch.empty((E, min(Tc, E - 1)), dtype=torch.int32, device="cuda"),
+             torch.empty((E,), dtype=torch.int64, device="cuda"))
+    torch.cuda.synchronize()
+    t_gen = time.time() - t_gen
+    mk = lambda: torch.cuda.Event(enable_timing=True)
+    names = ("select", "zero_C", "coactivation", "collaborators")
+
+    def step(tr=None):
+        def run(name, fn):
+            if tr is not None and name in tr:
+                tr[name][0].record()
+            fn()
+            if tr is not None and name in tr:
+                tr[name][1].record()
+        run("select", lambda: c2r.route_from_logits(lg, K, None, out=(idx, gates)))
+        run("zero_C", lambda: Cm.zero_())
+        run("coactivation", lambda: c2r.build_coactivation(idx, E, Cm))
+        run("collaborators", lambda: c2r.collaborators(Cm, Tc, out=lists))
+
+    t_ramp, ramp_steps = time.perf_counter(), 0
+    while (time.perf_counter() - t_ramp) * 1e3 < args.ramp_ms:
+        for _ in range(8):
+            step()
+        torch.cuda.synchronize()
+        ramp_steps += 8
+    for _ in range(args.warmup):
+        step()
+    ev_every = 4 if args.steps >= 8 else 1
+    ev_dom = [{"select": (mk(), mk())} if i % ev_every == 0 else None for i in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(ev_dom[i])
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+    dom_ms = float(np.mean([e["select"][0].elapsed_time(e["select"][1]) for e in ev_dom if e is not None]))
+    ev = [{n: (mk(), mk()) for n in names} for _ in range(args.steps)]
+    for i in range(args.steps):
+        step(ev[i])
+    torch.cuda.synchronize()
+    st_ms = {n: float(np.mean([e[n][0].elapsed_time(e[n][1]) for e in ev])) for n in names}
+    # algorithmic bytes: the logits are read once, indices and gates written, the indices read again
+    sel_bytes = T * (E * 4 + K * 8)
+    co_bytes = T * K * 4
+    stages = {"select": {"ms": st_ms["select"], "GBps": sel_bytes / st_ms["select"] / 1e6,
+                         "frac_hbm": sel_bytes / st_ms["select"] / 1e6 / PEAK["hbm_GBps"],
+                         "bytes": sel_bytes, "kernel": "route_select_kernel<60, ROWMAJOR>"},
+              "zero_C": {"ms": st_ms["zero_C"]},
+              "coactivation": {"ms": st_ms["coactivation"], "GBps": co_bytes / st_ms["coactivation"] / 1e6,
+                               "frac_hbm": co_bytes / st_ms["coactivation"] / 1e6 / PEAK["hbm_GBps"],
+                               "bytes": co_bytes, "increments_per_token": K * K, "kernel": "coactivation_kernel"},
+              "collaborators": {"ms": st_ms["collaborators"], "bound": "latency (60 x 60 integers)"}}
+    isolated = None
+    if args.isolate:
+        cold = ColdTimer(torch)
+        n_it = max(3, min(args.steps, 8))
+        isolated = {"device_copy_192MB": cold.copy_yardstick(n_it)}
+        for name, fn, nbytes in (("select", lambda: c2r.route_from_logits(lg, K, None, out=(idx, gates)), sel_bytes),
+                                 ("coactivation", lambda: c2r.build_coactivation(idx, E, Cm), co_bytes)):
+            isolated[name] = {}
+            for mode in ("after_write", "after_read"):
+                us = cold.time(lambda: None, fn, n_it, mode)
+                isolated[name][mode + "_us"] = us
+                isolated[name][mode + "_GBps"] = nbytes / us / 1e3
+                isolated[name][mode + "_frac_hbm"] = nbytes / us / 1e3 / PEAK["hbm_GBps"]
+        step()
+        torch.cuda.synchronize()
+    roofline = {"kernel": "route_select_kernel<60, ROWMAJOR> (top-K of stored logits)", "bound": "hbm",
+                "achieved": sel_bytes / dom_ms / 1e6, "peak": PEAK["hbm_GBps"], "unit": "GB/s",
+                "frac": sel_bytes / dom_ms / 1e6 / PEAK["hbm_GBps"], "traffic": None,
+                "avg_launch_ms": dom_ms, "launches_per_step": 1,
+                "launches_timed": sum(1 for e in ev_dom if e is not None),
+                "algorithmic_bytes_per_launch": sel_bytes,
+                "note": "the 252 MB logit stream fits the 256 MB memory-side cache, so back-to-back steps read part "
+                        "of it from there; stages_from_cold_memory has the same launch from cold memory",
+                "timed_by": "event pairs on the launch stream around every fourth step's launch"}
+    cpu = None
+    if args.cpu_sample > 0:
+        from oracle import c2r_oracle as orc
+        n = min(max(args.cpu_sample, 1) * 32, T)
+        tc = time.perf_counter()
+        idx_o, _ = orc.route(lg_h[:n], K)
+        C_o = orc.coactivation(idx_o, E)
+        lists_o = orc.collaborators(C_o, Tc)
+        tc = time.perf_counter() - tc
+        # the GPU on the same sample, compared bit for bit
+        ig, _ = c2r.route_from_logits(lg[:n].contiguous(), K, None)
+        Cg = c2r.build_coactivation(ig, E)
+        lg_lists, _ = c2r.collaborators(Cg, Tc)
+        cpu = {"value": n / tc, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": f"first {n} tokens of the logit stream through top-K, Eq. 2 and Eq. 4, {tc:.1f} s",
+               "indices_bit_exact": bool(np.array_equal(ig.cpu().numpy(), idx_o)),
+               "C_bit_exact": bool(np.array_equal(Cg.cpu().numpy().astype(np.int64), np.asarray(C_o, dtype=np.int64))),
+               "lists_bit_exact": bool(np.array_equal(lg_lists.cpu().numpy(), lists_o))}
+    out = {"metric": "C2R profiling tokens/sec (stored logits -> top-K -> co-activation -> collaborator lists)",
+           "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "clock_ramp_steps_before_warmup": ramp_steps, "ms_per_step": ms_per_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+           "config": {"workload": f"{w.name}: T={T} tokens of fp32 logits over E={E}, K={K}, lists of {Tc}; "
+                                  f"planted {w.groups}-group logit law"},
+           "roofline": roofline, "cpu_baseline": cpu, "stages": stages, "setup_s": t_gen}
+    if isolated is not None:
+        out["stages_from_cold_memory"] = isolated
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -29,13 +247,16 @@ def main():
     ap.add_argument("--ramp-ms", type=float, default=300.0,
                     help="run the step for this long before the warm-up steps: from idle the chip takes ~50 ms "
                          "under load to settle its clocks, and steps inside that ramp run 5-15 %% slower")
-    ap.add_argument("--workload", default="C3", help="C1|C2|C3|C5 (C3 = Qwen1.5-MoE-A2.7B-shaped layer)")
+    ap.add_argument("--workload", default="C3",
+                    help="C1|C2|C3|C5 (C3 = Qwen1.5-MoE-A2.7B-shaped layer) or C4 (profiling only: stored "
+                         "logits -> top-K -> co-activation matrix -> collaborator lists)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0: skip)")
     ap.add_argument("--overlap", action="store_true",
                     help="run the shared expert on a second stream (stage spans then overlap)")
-    ap.add_argument("--isolate", action="store_true",
-                    help="also time every stage on its own with a 512 MiB cache-flushing write before each "
-                         "launch (the 256 MB memory-side cache otherwise serves back-to-back stages)")
+    ap.add_argument("--no-isolate", dest="isolate", action="store_false",
+                    help="skip the cold pass: every stage timed on its own behind a cache flush (the 256 MB "
+                         "memory-side cache otherwise serves back-to-back stages), once after a 512 MiB "
+                         "write and once after that write plus a 1 GiB read")
     ap.add_argument("--hash-inputs", action="store_true", help="add the SHA-256 of every generated host array")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run plain device-to-device copies of known size (to scale rocprofv3's "
@@ -64,6 +285,8 @@ def main():
                           "copies": 10}))
         return
     w = wl.WORKLOADS[args.workload]
+    if w.F == 0:
+        return bench_profiling(args, w, torch, np, c2r, wl)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
     sz = 2 if w.dtype == "bf16" else 4
 
@@ -104,16 +327,8 @@ def main():
     # timed region: only the dominant kernel's launches carry events, and only on every fourth
     # step (an event record holds the stream for 5.6 us: fourteen per step were 3 % of the step,
     # the four around the two gate/up launches still 1.9 %)
-    # Where the dominant kernel is the fast bf16 one, its launches are timed by the dispatch's own
-    # time stamps instead (c2r_launch_timer_*): the kernel's duration without the markers' latency.
-    # A timed dispatch still costs the stream ~5 us before and after it (kernel trace), so these
-    # too are taken on every fourth step only.
-    use_timers = bool(L.fuse_gather and (not shared or L.split_shared))
     ev_every = 4 if args.steps >= 8 else 1
-    ev_dom = [{s: (mk(), mk()) for s in dom_stages} if (i % ev_every == 0 and not use_timers) else None
-              for i in range(args.steps)]
-    tm_dom = [{s: c2r.LaunchTimer() for s in dom_stages} if (i % ev_every == 0 and use_timers) else None
-              for i in range(args.steps)]
+    ev_dom = [{s: (mk(), mk()) for s in dom_stages} if i % ev_every == 0 else None for i in range(args.steps)]
     ev = [{s: (mk(), mk()) for s in stages} for _ in range(args.steps)]
 
     # clock ramp (not a measurement): from idle, the first ~50 ms of kernels run at lower clocks
@@ -129,18 +344,14 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        L.forward(x, trace=ev_dom[i], timers=tm_dom[i])
+        L.forward(x, trace=ev_dom[i])
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tokens_per_s = w.T / (ms_per_step * 1e-3)
-    if use_timers:
-        dom_ms_live = {s: float(np.mean([t[s].elapsed_ms() for t in tm_dom if t is not None])) for s in dom_stages}
-        dom_launches_timed = sum(len(dom_stages) for t in tm_dom if t is not None)
-    else:
-        dom_ms_live = {s: float(np.mean([e[s][0].elapsed_time(e[s][1]) for e in ev_dom if e is not None]))
-                       for s in dom_stages}
-        dom_launches_timed = sum(len(dom_stages) for e in ev_dom if e is not None)
+    dom_ms_live = {s: float(np.mean([e[s][0].elapsed_time(e[s][1]) for e in ev_dom if e is not None]))
+                   for s in dom_stages}
+    dom_launches_timed = sum(len(dom_stages) for e in ev_dom if e is not None)
 
     # stage breakdown: the same steps again, every stage bracketed by events (not part of `value`)
     for i in range(args.steps):
@@ -297,12 +508,15 @@ def main():
                                             if L.overlap else "sum of the four launches"}
 
     # HBM traffic of the dominant kernel per launch, from the committed rocprofv3 --pmc summary (if any)
-    traffic = None
+    traffic, traffic_src = None, None
     tfile = os.path.join(ROOT, "profiles", f"ffn_gate_up_{w.name}_hbm_traffic.txt")
     if os.path.exists(tfile):
         for line in open(tfile):
             if line.startswith("traffic_bytes_per_launch:"):
                 traffic = float(line.split(":")[1])
+            if line.startswith("measured_at_commit:"):
+                traffic_src = f"profiles/{os.path.basename(tfile)} (counters of a separate rocprofv3 --pmc run, " \
+                              f"library at commit {line.split(':')[1].strip()})"
     # dominant kernel: the gate/up pass (launched for the routed groups and, if any, the shared expert)
     n_launch = 2 if shared else 1
     dom_ms = sum(dom_ms_live.values()) / n_launch   # from the timed region
@@ -323,61 +537,51 @@ def main():
         roofline = {"kernel": "ffn_bf16_dma_kernel<0>" + both + " (gate/up + SwiGLU)", "bound": "mfma",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["mfma_bf16_TFLOPs"], "unit": "TFLOP/s",
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["mfma_bf16_TFLOPs"], "traffic": traffic,
+                    "traffic_source": traffic_src,
                     "avg_launch_ms": dom_ms, "launches_per_step": n_launch, "launches_timed": dom_launches_timed,
-                    "timed_by": "dispatch time stamps (c2r_launch_timer)" if use_timers else "stream events"}
+                    "timed_by": "event pairs on the launch stream around every fourth step's launches, inside the "
+                                "timed region (a pair brackets the marker latency too: a few per cent more than "
+                                "the kernel's own duration in the rocprofv3 trace)"}
     else:
         roofline = {"kernel": "ffn_f32_kernel<0>" + both + " (gate/up + SwiGLU)", "bound": "alu",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["valu_f32_TFLOPs"], "unit": "TFLOP/s",
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["valu_f32_TFLOPs"], "traffic": None,
                     "avg_launch_ms": dom_ms, "launches_per_step": n_launch, "launches_timed": dom_launches_timed}
 
-    # ---- measured ceilings of this machine: matrix pipe (zeros / random operands) and a device copy ----
-    def measured_ceilings():
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        out_p = torch.empty(1024 * 512, dtype=torch.float32, device="cuda")
-        res = {}
-        g = torch.Generator(device="cpu").manual_seed(7)
-        for name, ops in (("mfma_bf16_zero_operands_TFLOPs", torch.zeros(1024 * 8, dtype=torch.bfloat16)),
-                          ("mfma_bf16_random_operands_TFLOPs",
-                           (torch.rand(1024 * 8, generator=g) * 2 - 1).to(torch.bfloat16))):
-            ops = ops.cuda()
-            clk = torch.zeros(2, dtype=torch.int64, device="cuda")
-            c2r.probe_mfma_bf16(ops, 2000, 1024, out_p)
-            e0.record()
-            fl = c2r.probe_mfma_bf16(ops, 20000, 1024, out_p, clk)
-            e1.record()
-            torch.cuda.synchronize()
-            res[name] = fl / e0.elapsed_time(e1) / 1e9
-            cyc, ticks = clk.tolist()   # shader cycles / 100 MHz ticks of the loop: the clock under this load
-            res[name.replace("_TFLOPs", "_shader_clock_GHz")] = cyc / (ticks / 1e8) / 1e9 if ticks else None
-        src = torch.full(((512 << 20) // 4,), 1.0, dtype=torch.float32, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        e0.record()
-        for _ in range(5):
-            dst.copy_(src)
-        e1.record()
-        torch.cuda.synchronize()
-        res["copy_read_plus_write_GBps"] = 5 * 2 * (512 << 20) / e0.elapsed_time(e1) / 1e6
-        return res
+    ceilings = measured_ceilings(torch)
 
-    ceilings = measured_ceilings()
-
-    # ---- every stage on its own behind a cache flush ----
+    # ---- every stage on its own from cold memory (see ColdTimer) ----
     isolated = None
     if args.isolate:
-        flush = torch.empty((512 << 20) // 4, dtype=torch.float32, device="cuda")
-        n_it = max(3, min(args.steps, 10))
-        tot = {s: 0.0 for s in stages}
+        cold = ColdTimer(torch)
+        n_it = max(3, min(args.steps, 8))
+        isolated = {"protocols": ColdTimer.__doc__.split("Two protocols, because")[0].strip() +
+                                 " after_write: 512 MiB fill before the launch; after_read: that fill, then a 1 GiB read.",
+                    "device_copy_192MB": cold.copy_yardstick(n_it)}
         for s_name in stages:
-            for _ in range(n_it):
-                L.forward(x)                      # inputs of the stage are those of a real step
-                flush.fill_(1.0)                  # 512 MiB written: nothing of the step stays cached
-                pair = (mk(), mk())
-                L.forward(x, trace={s_name: pair}, only=s_name)
-                torch.cuda.synchronize()
-                tot[s_name] += pair[0].elapsed_time(pair[1])
-        isolated = {s_name: {"ms": tot[s_name] / n_it} for s_name in stages}
+            isolated[s_name] = {}
+            for mode in ("after_write", "after_read"):
+                pair = {}
+
+                def launch():
+                    pair["p"] = (mk(), mk())
+                    L.forward(x, trace={s_name: pair["p"]}, only=s_name)
+                # prepare: a real step leaves the stage's inputs in place
+                us = cold.time(lambda: L.forward(x), launch, n_it, mode)
+                isolated[s_name][mode + "_us"] = us
+        for s_name, nbytes in (("route", route_bytes), ("combine", comb_bytes)):
+            for mode in ("after_write", "after_read"):
+                us = isolated[s_name][mode + "_us"]
+                isolated[s_name][mode + "_GBps"] = nbytes / us / 1e3
+                isolated[s_name][mode + "_frac_hbm"] = nbytes / us / 1e3 / PEAK["hbm_GBps"]
+                isolated[s_name][mode + "_frac_of_copy"] = (nbytes / us / 1e3) / isolated["device_copy_192MB"][mode]["GBps"]
+        # the ABI's stand-alone dispatch with the row scatter
+        for mode in ("after_write", "after_read"):
+            us = cold.time(lambda: None, lambda: c2r.permute(x, L.idx, L.E, L.local_slot, L.E_local, ws=L.ws_perm,
+                           out=(L.counts, L.offsets, L.perm, L.inv_perm, x_perm_sa)), n_it, mode)
+            isolated.setdefault("permute_standalone_with_rows", {})[mode + "_us"] = us
+            isolated["permute_standalone_with_rows"][mode + "_GBps"] = perm_bytes / us / 1e3
+            isolated["permute_standalone_with_rows"][mode + "_frac_hbm"] = perm_bytes / us / 1e3 / PEAK["hbm_GBps"]
 
     input_hashes = None
     if args.hash_inputs:
@@ -425,7 +629,7 @@ def main():
         "setup_s": t_gen,
     }
     if isolated is not None:
-        out["stages_isolated_after_cache_flush"] = isolated
+        out["stages_from_cold_memory"] = isolated
     if input_hashes is not None:
         out["inputs"] = {"seed_base": wl.SEED_BASE if hasattr(wl, "SEED_BASE") else None, "arrays": input_hashes}
     print(json.dumps(out))

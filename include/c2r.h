@@ -83,7 +83,11 @@ size_t c2r_workspace_bytes(int stage, int64_t T, int d, int E, int K, int F, c2r
  *            are ignored, so a token padded with -1 counts for fewer experts)
  * C        : int32[E, E]  in/out.  ACCUMULATES, so a corpus can be profiled
  *            batch by batch; the caller zeroes it before the first batch.
- * Result is exact and independent of scheduling (integer adds).
+ * Result is exact and independent of scheduling (integer adds) as long as no
+ * entry passes 2^31 - 1: the adds wrap, they do not saturate.  The largest entry
+ * is a diagonal one (tokens that selected that expert), so a corpus of fewer
+ * than 2^31 tokens cannot overflow; beyond that, fold C into a wider host-side
+ * matrix between batches.
  */
 int c2r_build_coactivation(const int32_t *topk_idx, int64_t T, int K, int E, int32_t *C,
                            void *stream);
@@ -307,47 +311,6 @@ int c2r_collaboration_degree(const int32_t *C, int E, double *P, void *stream);
  */
 int c2r_distinct_devices(const int32_t *topk_idx, int64_t T, int K, int E, const int32_t *expert_device,
                          int n_maps, int n_dev, int32_t *per_token, int64_t *totals, void *stream);
-
-/*
- * Measurement aid, not a step of the path (Sec. 4 reports efficiency; no passage defines
- * this operation): a loop of independent bf16 matrix instructions
- * (v_mfma_f32_16x16x32_bf16) on register operands, used by the benchmark to report the
- * matrix pipe's measured ceiling on this chip next to the vendor peak.
- * operands : 1024 x 16 bytes of bf16 in DEVICE memory (values set the power drawn:
- *            zeros reach the clock-limited peak, random values are power limited)
- * iters    : loop trips; every wave issues 8 matrix instructions per trip
- * blocks   : workgroups of 512 threads (1..65536)
- * out      : float[blocks * 512] in DEVICE memory (sums, so the loop is not removed)
- * flops    : HOST pointer or NULL; receives the floating-point operations of the launch
- * clocks   : uint64[2] in DEVICE memory or NULL; receives, from one thread of the first
- *            workgroup, the shader cycles and the ticks of the constant 100 MHz clock that the
- *            loop took: cycles / (ticks / 1e8) is the clock the chip really ran at
- */
-int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops, uint64_t *clocks,
-                        void *stream);
-
-/*
- * Measurement aid, not a step of the path: the duration of ONE launch of the fast bf16
- * expert-FFN kernel (bf16, d a multiple of 64), taken from the dispatch's own start and end
- * time stamps.  Stream markers around a launch measure their own latency too (about 5 % more
- * than the kernel at 0.35 ms); these time stamps are the kernel's.  A timed launch still costs
- * the stream a few microseconds before and after it, so a benchmark times a sample of its
- * launches, not all of them.
- *   create   : makes a timer (a HOST object holding two events; the one exception to "the
- *              library allocates nothing": no device memory is involved)
- *   arm      : the next such launch enqueued by THIS host thread (by c2r_expert_ffn,
- *              _gate_up, _gate_up_gather or _down; for c2r_expert_ffn the first of its two
- *              passes) records into the timer; arming again before a launch replaces the
- *              previous arming.  Launches of the other FFN kernels (fp32, generic bf16) do not
- *              take a timer.
- *   elapsed  : waits for that launch to finish and returns its duration in milliseconds;
- *              C2R_ERR_INVALID_ARG if no launch has taken the timer since it was armed
- *   destroy  : frees the timer (disarming it if armed)
- */
-int c2r_launch_timer_create(void **timer);
-int c2r_launch_timer_arm(void *timer);
-int c2r_launch_timer_elapsed_ms(void *timer, float *ms);
-int c2r_launch_timer_destroy(void *timer);
 
 #ifdef __cplusplus
 }

@@ -1,9 +1,22 @@
+// Benchmark equipment, NOT part of the C2R library or its ABI: built into its own shared
+// object (libc2r_benchaid.so) that only bench.py loads.
 // Measured ceiling of the matrix pipe on this chip: a loop of independent
 // v_mfma_f32_16x16x32_bf16 on register operands, nothing else.  The benchmark reports it
 // next to the vendor peak (on random operands the chip is power limited well below it).
-#include "c2r_internal.h"
+//   operands : 1024 x 16 bytes of bf16 in DEVICE memory (zeros reach the clock-limited peak,
+//              random values are power limited)
+//   iters    : loop trips; every wave issues 8 matrix instructions per trip
+//   blocks   : workgroups of 512 threads (1..65536)
+//   out      : float[blocks * 512] in DEVICE memory (sums, so the loop is not removed)
+//   flops    : HOST pointer or NULL; receives the floating-point operations of the launch
+//   clocks   : uint64[2] in DEVICE memory or NULL; receives, from one thread of the first
+//              workgroup, the shader cycles and the ticks of the constant 100 MHz clock that
+//              the loop took: cycles / (ticks / 1e8) is the clock the chip really ran at
+// Returns 0, or -1 for a bad argument, -4 if the launch was refused.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
 
-namespace c2r {
+namespace benchaid {
 
 typedef __bf16 probe_bf16x8 __attribute__((ext_vector_type(8)));
 typedef float probe_f32x4 __attribute__((ext_vector_type(4)));
@@ -43,16 +56,16 @@ __global__ __launch_bounds__(PROBE_THREADS) void probe_mfma_kernel(const probe_b
     out[(size_t)blockIdx.x * PROBE_THREADS + threadIdx.x] = s;
 }
 
-}  // namespace c2r
+}  // namespace benchaid
 
-using namespace c2r;
+using namespace benchaid;
 
-extern "C" int c2r_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops,
+extern "C" int benchaid_probe_mfma_bf16(const void *operands, int iters, int blocks, float *out, double *flops,
                                    uint64_t *clocks, void *stream) {
-    if (!operands || !out || iters < 1 || blocks < 1 || blocks > 65536) return C2R_ERR_INVALID_ARG;
-    if (!aligned(operands, 16) || !aligned(clocks, 8)) return C2R_ERR_INVALID_ARG;
+    if (!operands || !out || iters < 1 || blocks < 1 || blocks > 65536) return -1;
+    if (reinterpret_cast<uintptr_t>(operands) % 16 || reinterpret_cast<uintptr_t>(clocks) % 8) return -1;
     probe_mfma_kernel<<<dim3((unsigned)blocks), dim3(PROBE_THREADS), 0, static_cast<hipStream_t>(stream)>>>(
         static_cast<const probe_bf16x8 *>(operands), iters, out, reinterpret_cast<unsigned long long *>(clocks));
     if (flops) *flops = (double)blocks * (PROBE_THREADS / 64) * (double)iters * PROBE_ACC * (2.0 * 16 * 16 * 32);
-    return launch_status();
+    return hipGetLastError() == hipSuccess ? 0 : -4;
 }

@@ -14,7 +14,10 @@ CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libc2r_hip.so")
 OBJ = os.path.join(HERE, "_build")
 SOURCES = ["api.hip", "route.hip", "coact.hip", "permute.hip", "combine.hip", "ffn_f32.hip", "ffn_bf16.hip", "ffn_bf16_dma.hip",
-           "dedup.hip", "metrics.hip", "probe.hip"]
+           "dedup.hip", "metrics.hip"]
+# benchmark equipment (a matrix-pipe ceiling probe): its own library, loaded by bench.py only
+AID_SRC = os.path.join(HERE, "bench_aids", "probe.hip")
+AID_OUT = os.path.join(HERE, "bench_aids", "libc2r_benchaid.so")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
@@ -36,6 +39,9 @@ def build(jobs: int = 4) -> str:
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(_compile, SOURCES))
     subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", OUT, *objs], check=True)
+    r = subprocess.run(["hipcc", *FLAGS, "-shared", "-o", AID_OUT, AID_SRC], capture_output=True, text=True)
+    if r.returncode != 0:
+        raise RuntimeError(f"hipcc failed on {AID_SRC}:\n{r.stderr}")
     return OUT
 
 

@@ -26,8 +26,7 @@ EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_c
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_gather", "c2r_expert_ffn_down",
            "c2r_combine",
            "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies",
-           "c2r_collaboration_degree", "c2r_distinct_devices", "c2r_probe_mfma_bf16",
-           "c2r_launch_timer_create", "c2r_launch_timer_arm", "c2r_launch_timer_elapsed_ms", "c2r_launch_timer_destroy"]
+           "c2r_collaboration_degree", "c2r_distinct_devices"]
 
 
 class C2RError(RuntimeError):
@@ -69,11 +68,6 @@ def lib():
         L.c2r_combine_copies.argtypes = [vp, i32, vp, i64, i64, i32, i32, vp, vp, vp]
         L.c2r_collaboration_degree.argtypes = [vp, i32, vp, vp]
         L.c2r_distinct_devices.argtypes = [vp, i64, i32, i32, vp, i32, i32, vp, vp, vp]
-        L.c2r_probe_mfma_bf16.argtypes = [vp, i32, i32, vp, C.POINTER(C.c_double), vp, vp]
-        L.c2r_launch_timer_create.argtypes = [C.POINTER(vp)]
-        L.c2r_launch_timer_arm.argtypes = [vp]
-        L.c2r_launch_timer_elapsed_ms.argtypes = [vp, C.POINTER(C.c_float)]
-        L.c2r_launch_timer_destroy.argtypes = [vp]
         for name in EXPORTS[3:]:
             getattr(L, name).restype = i32
         _lib = L
@@ -132,12 +126,15 @@ def build_coactivation(topk_idx: torch.Tensor, E: int, Cm: Optional[torch.Tensor
     return Cm
 
 
-def collaborators(Cm: torch.Tensor, Tc: int):
+def collaborators(Cm: torch.Tensor, Tc: int, out=None):
     """Eq. 4.  Returns (collab_idx int32[E, min(Tc,E-1)], collab_mask int64[E])."""
     E = Cm.shape[0]
     n = min(Tc, E - 1)
-    idx = torch.empty((E, n), dtype=torch.int32, device=Cm.device)
-    mask = torch.empty((E,), dtype=torch.int64, device=Cm.device)
+    if out is None:
+        idx = torch.empty((E, n), dtype=torch.int32, device=Cm.device)
+        mask = torch.empty((E,), dtype=torch.int64, device=Cm.device)
+    else:
+        idx, mask = out
     _check("c2r_collaborators", lib().c2r_collaborators(_ptr(Cm), E, Tc, _ptr(idx), _ptr(mask), _stream()))
     return idx, mask
 
@@ -161,10 +158,13 @@ def route(x, Wg, bias, K, collab_idx=None, want_logits=False, ws=None, out=None)
     return idx, gates, logits
 
 
-def route_from_logits(logits, K, collab_idx=None):
+def route_from_logits(logits, K, collab_idx=None, out=None):
     T, E = logits.shape
-    idx = torch.empty((T, K), dtype=torch.int32, device=logits.device)
-    gates = torch.empty((T, K), dtype=torch.float32, device=logits.device)
+    if out is None:
+        idx = torch.empty((T, K), dtype=torch.int32, device=logits.device)
+        gates = torch.empty((T, K), dtype=torch.float32, device=logits.device)
+    else:
+        idx, gates = out
     Tc = 0 if collab_idx is None else collab_idx.shape[1]
     _check("c2r_route_from_logits", lib().c2r_route_from_logits(_ptr(logits), T, E, K, _ptr(collab_idx), Tc,
                                                                  _ptr(idx), _ptr(gates), _stream()))
@@ -336,40 +336,6 @@ def distinct_devices(topk_idx, E, expert_device, n_dev, per_token=False):
     return (totals, pt) if per_token else totals
 
 
-def probe_mfma_bf16(operands, iters, blocks, out, clocks=None):
-    """Measurement aid: a pure bf16 matrix-instruction loop.  Returns the launch's flops;
-    clocks (int64[2] on the device, optional) receives shader cycles and 100 MHz ticks."""
-    assert operands.numel() * operands.element_size() >= 1024 * 16 and out.numel() >= blocks * 512
-    assert clocks is None or (clocks.dtype == torch.int64 and clocks.numel() >= 2)
-    fl = C.c_double(0.0)
-    _check("c2r_probe_mfma_bf16", lib().c2r_probe_mfma_bf16(_ptr(operands), iters, blocks, _ptr(out), C.byref(fl),
-                                                          _ptr(clocks), _stream()))
-    return fl.value
-
-
-class LaunchTimer:
-    """Measurement aid: the duration of one launch of the fast bf16 expert-FFN kernel, from the
-    dispatch's own time stamps.  arm() before the call that launches it, elapsed_ms() after."""
-
-    def __init__(self):
-        h = C.c_void_p()
-        _check("c2r_launch_timer_create", lib().c2r_launch_timer_create(C.byref(h)))
-        self._h = h
-
-    def arm(self):
-        _check("c2r_launch_timer_arm", lib().c2r_launch_timer_arm(self._h))
-
-    def elapsed_ms(self) -> float:
-        ms = C.c_float()
-        _check("c2r_launch_timer_elapsed_ms", lib().c2r_launch_timer_elapsed_ms(self._h, C.byref(ms)))
-        return ms.value
-
-    def __del__(self):
-        if getattr(self, "_h", None) is not None and _lib is not None:
-            _lib.c2r_launch_timer_destroy(self._h)
-            self._h = None
-
-
 class C2RLayer:
     """One C2R MoE layer with all buffers allocated up front: forward() only
     enqueues the library's stages (no allocation, no host synchronisation).
@@ -436,12 +402,11 @@ class C2RLayer:
     # names of the stages forward() runs, in the order a trace lists them
     STAGES = ("route", "permute", "ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down", "combine")
 
-    def forward(self, x, trace=None, only=None, timers=None):
+    def forward(self, x, trace=None, only=None):
         """y = layer(x).  trace: optional {stage: (start_event, end_event)} for any subset of
         STAGES; each pair is recorded on the stream its stage runs on (timing events, made by
         the caller).  only: run just that stage on the buffers a previous full call left
-        (for timing a stage on its own).  timers: optional {stage: LaunchTimer}, armed before
-        the stage's call (stages that launch the fast bf16 FFN kernel)."""
+        (for timing a stage on its own)."""
         main = torch.cuda.current_stream()
         side = self.side if self.overlap else main
 
@@ -452,8 +417,6 @@ class C2RLayer:
             with torch.cuda.stream(stream):
                 if pair is not None:
                     pair[0].record(stream)
-                if timers is not None and name in timers:
-                    timers[name].arm()
                 fn()
                 if pair is not None:
                     pair[1].record(stream)

@@ -1,7 +1,5 @@
 // Host entry points that do not belong to a single kernel file: version,
 // workspace query, and the expert-FFN dispatcher (fp32 vector path / bf16 MFMA path).
-#include <new>
-
 #include "c2r_internal.h"
 
 namespace c2r {
@@ -166,53 +164,4 @@ extern "C" int c2r_expert_ffn_gather(const void *x, c2r_dtype dt, const int32_t 
                                   static_cast<uint16_t *>(ws), ldh, perm, K, (int)T, static_cast<hipStream_t>(stream));
     if (rc != C2R_OK) return rc;
     return ffn_pass(1, dt, ws, offsets, E_local, A_cap, d, F, ldh, w_down, nullptr, y_perm, stream);
-}
-
-// ---- measurement aid: the duration of one launch, taken from the dispatch itself ----
-namespace c2r {
-thread_local LaunchTimer *armed_launch_timer = nullptr;
-}
-
-extern "C" int c2r_launch_timer_create(void **timer) {
-    if (!timer) return C2R_ERR_INVALID_ARG;
-    LaunchTimer *t = new (std::nothrow) LaunchTimer;
-    if (!t) return C2R_ERR_LAUNCH;
-    t->fired = false;
-    if (hipEventCreate(&t->start) != hipSuccess) {
-        delete t;
-        return C2R_ERR_LAUNCH;
-    }
-    if (hipEventCreate(&t->stop) != hipSuccess) {
-        (void)hipEventDestroy(t->start);
-        delete t;
-        return C2R_ERR_LAUNCH;
-    }
-    *timer = t;
-    return C2R_OK;
-}
-
-extern "C" int c2r_launch_timer_arm(void *timer) {
-    if (!timer) return C2R_ERR_INVALID_ARG;
-    LaunchTimer *t = static_cast<LaunchTimer *>(timer);
-    t->fired = false;
-    armed_launch_timer = t;
-    return C2R_OK;
-}
-
-extern "C" int c2r_launch_timer_elapsed_ms(void *timer, float *ms) {
-    if (!timer || !ms) return C2R_ERR_INVALID_ARG;
-    LaunchTimer *t = static_cast<LaunchTimer *>(timer);
-    if (!t->fired) return C2R_ERR_INVALID_ARG;  // armed (or not) but no launch has taken it
-    if (hipEventSynchronize(t->stop) != hipSuccess) return C2R_ERR_LAUNCH;
-    return hipEventElapsedTime(ms, t->start, t->stop) == hipSuccess ? C2R_OK : C2R_ERR_LAUNCH;
-}
-
-extern "C" int c2r_launch_timer_destroy(void *timer) {
-    if (!timer) return C2R_ERR_INVALID_ARG;
-    LaunchTimer *t = static_cast<LaunchTimer *>(timer);
-    if (armed_launch_timer == t) armed_launch_timer = nullptr;
-    (void)hipEventDestroy(t->start);
-    (void)hipEventDestroy(t->stop);
-    delete t;
-    return C2R_OK;
 }

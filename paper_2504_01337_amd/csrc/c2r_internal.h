@@ -11,8 +11,13 @@
 
 namespace c2r {
 
+// An error that the caller's own earlier HIP work left behind in this thread must not be blamed
+// on this library's launches: every entry point reads (and thereby clears) it before it
+// launches anything, and launch_status() then reports only what its own launches raised.
+static inline void drop_stale_error() { (void)hipGetLastError(); }
+
 static inline int launch_status() {
-    return hipPeekAtLastError() == hipSuccess ? C2R_OK : C2R_ERR_LAUNCH;
+    return hipGetLastError() == hipSuccess ? C2R_OK : C2R_ERR_LAUNCH;
 }
 
 static inline bool aligned(const void *p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -33,14 +38,6 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
 }
 
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) { return pack_bf16x2(f, 0.0f) & 0xffffu; }
-
-// Measurement aid (c2r_launch_timer_*): a pair of events that the next launch of the fast bf16
-// expert-FFN kernel on this host thread attaches to its dispatch.
-struct LaunchTimer {
-    hipEvent_t start, stop;
-    bool fired;
-};
-extern thread_local LaunchTimer *armed_launch_timer;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (C2R_WAVE - 1); }
 

@@ -147,6 +147,7 @@ __global__ __launch_bounds__(64) void place_experts_kernel(const int32_t *__rest
 using namespace c2r;
 
 extern "C" int c2r_place_experts(const int32_t *C, int E, int n_dev, int32_t *expert_device, void *stream) {
+    drop_stale_error();
     if (E < 1 || n_dev < 1) return C2R_ERR_INVALID_ARG;
     if (E > C2R_MAX_E || n_dev > C2R_MAX_E) return C2R_ERR_UNSUPPORTED;
     if (!C || !expert_device) return C2R_ERR_INVALID_ARG;
@@ -156,6 +157,7 @@ extern "C" int c2r_place_experts(const int32_t *C, int E, int n_dev, int32_t *ex
 
 extern "C" int c2r_build_coactivation(const int32_t *topk_idx, int64_t T, int K, int E, int32_t *C,
                                       void *stream) {
+    drop_stale_error();
     if (T < 0 || K < 1 || E < 1) return C2R_ERR_INVALID_ARG;
     if (E > C2R_MAX_E) return C2R_ERR_UNSUPPORTED;
     if (T == 0) return C2R_OK;
@@ -179,6 +181,7 @@ extern "C" int c2r_build_coactivation(const int32_t *topk_idx, int64_t T, int K,
 
 extern "C" int c2r_collaborators(const int32_t *C, int E, int Tc, int32_t *collab_idx,
                                  uint64_t *collab_mask, void *stream) {
+    drop_stale_error();
     if (E < 1 || Tc < 0) return C2R_ERR_INVALID_ARG;
     if (E > C2R_MAX_E) return C2R_ERR_UNSUPPORTED;
     if (!C || (!collab_idx && !collab_mask)) return C2R_ERR_INVALID_ARG;

@@ -63,6 +63,7 @@ using namespace c2r;
 extern "C" int c2r_combine(const void *y_perm, c2r_dtype dt, const float *gates,
                            const int32_t *inv_perm, int64_t T, int d, int K, const void *y_shared,
                            void *y, void *stream) {
+    drop_stale_error();
     if (T < 0 || d < 1 || K < 1) return C2R_ERR_INVALID_ARG;
     if (dt != C2R_F32 && dt != C2R_BF16) return C2R_ERR_INVALID_ARG;
     if (T == 0) return C2R_OK;

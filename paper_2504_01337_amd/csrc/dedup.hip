@@ -295,13 +295,14 @@ using namespace c2r;
 extern "C" int c2r_dedup_dispatch(const int32_t *topk_idx, int64_t T, int K, int E, const int32_t *expert_device,
                                   int n_dev, int32_t *send_counts, int32_t *send_offsets, int32_t *send_token,
                                   int32_t *send_row, void *ws, size_t ws_bytes, void *stream) {
+    drop_stale_error();
     if (T < 0 || K < 1 || E < 1 || n_dev < 1) return C2R_ERR_INVALID_ARG;
     if (E > C2R_MAX_E || n_dev > C2R_MAX_E) return C2R_ERR_UNSUPPORTED;
     if (T * (int64_t)K >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (!expert_device || !send_counts || !send_offsets) return C2R_ERR_INVALID_ARG;
     if (T > 0 && (!topk_idx || !send_token || !send_row)) return C2R_ERR_INVALID_ARG;
     const size_t need = dedup_workspace_bytes(T > 0 ? T : 1, n_dev);
-    if (!ws || ws_bytes < need) return C2R_ERR_WORKSPACE;
+    if (!ws || ws_bytes < need || !aligned(ws, 256)) return C2R_ERR_WORKSPACE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t nblocks = T > 0 ? (T + DB_SPAN - 1) / DB_SPAN : 1;
     if (nblocks >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
@@ -317,6 +318,7 @@ extern "C" int c2r_dedup_dispatch(const int32_t *topk_idx, int64_t T, int K, int
 extern "C" int c2r_combine_partial(const void *y_perm, c2r_dtype dt, const float *gates, const int32_t *inv_perm,
                                    const int32_t *send_token, const int32_t *send_row, const int32_t *n_send,
                                    int64_t T, int64_t cap_rows, int d, int K, void *y_part, void *stream) {
+    drop_stale_error();
     if (T < 0 || cap_rows < 0 || d < 1 || K < 1) return C2R_ERR_INVALID_ARG;
     if (dt != C2R_F32 && dt != C2R_BF16) return C2R_ERR_INVALID_ARG;
     if (T == 0 || cap_rows == 0) return C2R_OK;
@@ -340,6 +342,7 @@ extern "C" int c2r_combine_partial(const void *y_perm, c2r_dtype dt, const float
 
 extern "C" int c2r_combine_copies(const void *y_part, c2r_dtype dt, const int32_t *send_row, int64_t T,
                                   int64_t cap_rows, int d, int K, const void *y_shared, void *y, void *stream) {
+    drop_stale_error();
     if (T < 0 || cap_rows < 0 || d < 1 || K < 1) return C2R_ERR_INVALID_ARG;
     if (dt != C2R_F32 && dt != C2R_BF16) return C2R_ERR_INVALID_ARG;
     if (T == 0) return C2R_OK;

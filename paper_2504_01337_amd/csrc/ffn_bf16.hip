@@ -198,6 +198,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_kernel(const uint16_t *_
 template <int BM, int BN, int BK, int WM, int WN>
 static int launch_cfg(int pass, const uint16_t *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
                       int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out, hipStream_t st) {
+    drop_stale_error();
     const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
     const int ntn = pass == 0 ? (F + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
     const int64_t grid = xcd_grouped_grid(mtiles, ntn, false);

@@ -22,8 +22,6 @@
 // chunk 0 of the same row and multiplied by those zeros.
 #include <type_traits>
 
-#include <hip/hip_ext.h>
-
 #include "ffn_common.h"
 
 namespace c2r {
@@ -612,6 +610,7 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
                              int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1,
                              uint16_t *out, int ldo, const int32_t *gather, int gather_div, int gather_rows,
                              hipStream_t st) {
+    drop_stale_error();
     constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
     const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
     const int ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
@@ -620,18 +619,7 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
     const dim3 g((unsigned)grid), b(WM * WN * 64);
     const uint16_t *no_b1 = nullptr;
     const int32_t *no_gather = nullptr;
-    if (LaunchTimer *t = armed_launch_timer) {
-        // a timed launch: the dispatch itself records its start and its end into the timer's events
-        armed_launch_timer = nullptr;
-        if (pass == 0)
-            hipExtLaunchKernelGGL((ffn_bf16_dma_kernel<0, WM, WN>), g, b, 0, st, t->start, t->stop, 0, a, lda, offsets,
-                                  E_local, (int)A_cap, F, d, b0, b1, out, ldo, ntn, ldo, gather, gather_div,
-                                  gather_rows);
-        else
-            hipExtLaunchKernelGGL((ffn_bf16_dma_kernel<1, WM, WN>), g, b, 0, st, t->start, t->stop, 0, a, lda, offsets,
-                                  E_local, (int)A_cap, d, F, b0, no_b1, out, ldo, ntn, 0, no_gather, 1, 1);
-        t->fired = true;
-    } else if (pass == 0) {
+    if (pass == 0) {
         ffn_bf16_dma_kernel<0, WM, WN><<<g, b, 0, st>>>(a, lda, offsets, E_local, (int)A_cap, F, d, b0, b1, out, ldo,
                                                         ntn, ldo, gather, gather_div, gather_rows);
     } else {

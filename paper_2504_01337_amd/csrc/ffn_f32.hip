@@ -90,6 +90,7 @@ __global__ __launch_bounds__(256) void ffn_f32_kernel(const float *__restrict__ 
 
 int launch_ffn_f32_pass(int pass, const float *a, const int32_t *offsets, int E_local, int64_t A_cap, int d,
                         int F, const float *b0, const float *b1, float *out, hipStream_t st) {
+    drop_stale_error();
     const int64_t mtiles = (A_cap + F32_BM - 1) / F32_BM + E_local;
     const int N = pass == 0 ? F : d;
     const int64_t grid = mtiles * ((N + F32_BN - 1) / F32_BN);

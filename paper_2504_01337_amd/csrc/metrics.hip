@@ -87,6 +87,7 @@ __global__ __launch_bounds__(256) void distinct_devices_kernel(
 using namespace c2r;
 
 extern "C" int c2r_collaboration_degree(const int32_t *C, int E, double *P, void *stream) {
+    drop_stale_error();
     if (E < 1) return C2R_ERR_INVALID_ARG;
     if (E > C2R_MAX_E) return C2R_ERR_UNSUPPORTED;
     if (!C || !P) return C2R_ERR_INVALID_ARG;
@@ -97,6 +98,7 @@ extern "C" int c2r_collaboration_degree(const int32_t *C, int E, double *P, void
 extern "C" int c2r_distinct_devices(const int32_t *topk_idx, int64_t T, int K, int E,
                                     const int32_t *expert_device, int n_maps, int n_dev,
                                     int32_t *per_token, int64_t *totals, void *stream) {
+    drop_stale_error();
     if (T < 0 || K < 1 || E < 1 || n_maps < 1 || n_dev < 1) return C2R_ERR_INVALID_ARG;
     if (E > C2R_MAX_E || n_dev > C2R_MAX_E || n_maps > MAX_MAPS) return C2R_ERR_UNSUPPORTED;
     if (!totals || !expert_device || (T > 0 && !topk_idx)) return C2R_ERR_INVALID_ARG;

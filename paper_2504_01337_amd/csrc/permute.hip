@@ -308,6 +308,7 @@ extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx,
                            int E, int K, const int32_t *local_slot, int E_local, int32_t *counts,
                            int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
                            void *ws, size_t ws_bytes, void *stream) {
+    drop_stale_error();
     if (T < 0 || E < 1 || K < 1 || E_local < 1 || E_local > E) return C2R_ERR_INVALID_ARG;
     if (!local_slot && E_local != E) return C2R_ERR_INVALID_ARG;
     if (dt != C2R_F32 && dt != C2R_BF16) return C2R_ERR_INVALID_ARG;

@@ -446,7 +446,8 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
             for (int j = 0; j < 4; ++j) {
                 const uint32_t f = (uint32_t)i + j;
                 if (f < nflt) {
-                    const uint32_t r = __umulhi(f, rcp);  // f / E, exact for f < 4096
+                    // f / E, exact for f < 4096 (the 32-bit reciprocal of 1 does not exist)
+                    const uint32_t r = E == 1 ? f : __umulhi(f, rcp);
                     tl[r * LP + (f - r * E)] = v[j];
                 }
             }
@@ -669,6 +670,7 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
                          int64_t T, int d, int E, int K, const int32_t *collab_idx, int Tc,
                          int32_t *topk_idx, float *gates, float *logits_out, void *ws,
                          size_t ws_bytes, void *stream) {
+    drop_stale_error();
     int rc = check_route_args(T, E, K, collab_idx, Tc);
     if (rc != C2R_OK) return rc;
     if (d < 1 || (x_dt != C2R_F32 && x_dt != C2R_BF16)) return C2R_ERR_INVALID_ARG;
@@ -703,7 +705,8 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
     const int64_t nwt = wide ? ntiles : ntiles * 2;
     const int64_t nblk = (nwt + NWV - 1) / NWV * L.nchunk;
     if (nblk >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
-    // more than 8 experts: the matrix pipe, a wave covering 32 or 64 experts (padded with zero columns)
+    // more than 8 experts: the matrix pipe, a wave covering 32 or 64 experts (columns past the packed
+    // expert count re-read column 0; their sums are never stored)
 #define C2R_ROUTE_LAUNCH(BF, TE, NWV, TQ, MF)                                                     \
     route_partial_kernel<BF, TE, NWV, TQ, MF><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(    \
         x, W, ldw, L.EP, T, d, L.nchunk, ntiles, part)
@@ -729,6 +732,7 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
 extern "C" int c2r_route_from_logits(const float *logits, int64_t T, int E, int K,
                                      const int32_t *collab_idx, int Tc, int32_t *topk_idx,
                                      float *gates, void *stream) {
+    drop_stale_error();
     int rc = check_route_args(T, E, K, collab_idx, Tc);
     if (rc != C2R_OK) return rc;
     if (T == 0) return C2R_OK;

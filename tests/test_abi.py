@@ -78,11 +78,7 @@ def test_argument_errors_before_launch():
     assert L.c2r_combine_partial(p, 1, p, p, p, p, p, 16, 32, 60, 2, p, null) == c2r.ERR_UNSUPPORTED
     assert L.c2r_combine_partial(p, 1, p, p, p, p, null, 16, 32, 64, 2, p, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_combine_copies(p, 1, null, 16, 32, 64, 2, null, p, null) == c2r.ERR_INVALID_ARG
-    assert L.c2r_probe_mfma_bf16(p, 0, 4, p, None, null, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_collaboration_degree(p, 65, p, null) == c2r.ERR_UNSUPPORTED
-    assert L.c2r_launch_timer_arm(null) == c2r.ERR_INVALID_ARG
-    assert L.c2r_launch_timer_elapsed_ms(null, None) == c2r.ERR_INVALID_ARG
-    assert L.c2r_launch_timer_create(None) == c2r.ERR_INVALID_ARG
     assert L.c2r_collaboration_degree(p, 8, null, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_distinct_devices(p, 16, 2, 8, p, 9, 4, null, p, null) == c2r.ERR_UNSUPPORTED   # more than 8 maps
     assert L.c2r_distinct_devices(p, 16, 2, 8, p, 2, 4, null, null, null) == c2r.ERR_INVALID_ARG

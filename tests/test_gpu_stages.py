@@ -109,6 +109,19 @@ def test_route_from_logits(c2r, orc, E, K, Tc, T):
         np.testing.assert_allclose(host(gates), g_ref, rtol=2e-6, atol=1e-7)
 
 
+def test_route_from_logits_single_expert(c2r, orc):
+    # E = 1: every token selects expert 0; its gate is exp(l - l) / sum = 1 for a finite logit and
+    # NaN for an infinite or NaN one (the stated gate rule)
+    logits = np.random.default_rng(1).standard_normal((333, 1)).astype(np.float32)
+    logits[5, 0], logits[17, 0], logits[40, 0] = np.nan, np.inf, -np.inf
+    idx, gates = c2r.route_from_logits(dev(logits), 1, None)
+    idx_ref, g_ref = orc.route(logits, 1, None)
+    assert np.array_equal(host(idx), idx_ref) and not host(idx).any()
+    g = host(gates)
+    assert np.array_equal(np.isnan(g), np.isnan(g_ref)) and np.isnan(g[[5, 17, 40], 0]).all()
+    assert np.array_equal(g[~np.isnan(g)], np.ones(330, dtype=np.float32))
+
+
 def test_route_nan_logits_follow_the_stated_rule(c2r, orc):
     E, K = 12, 3
     logits = np.random.default_rng(5).standard_normal((200, E)).astype(np.float32)
@@ -330,24 +343,6 @@ def test_combine(c2r, orc, dtype, T, K, d):
         assert np.abs(host(y) - ref).max() <= tol * max(np.abs(ref).max(), 1.0)
 
 
-def test_probe_mfma_counts_its_work(c2r):
-    # operands all ones: every 16x16x32 matrix instruction adds 32 to each of the lane's 4
-    # accumulator values; 8 accumulators, 3 trips -> each thread's sum is 3 * 8 * 4 * 32
-    ops = torch.ones(1024 * 8, dtype=torch.bfloat16, device="cuda")
-    out = torch.zeros(4 * 512, dtype=torch.float32, device="cuda")
-    flops = c2r.probe_mfma_bf16(ops, 3, 4, out)
-    torch.cuda.synchronize()
-    assert flops == 4 * 8 * 3 * 8 * 2 * 16 * 16 * 32
-    assert torch.all(out == 3 * 8 * 4 * 32)
-    # with clock stamps: a longer loop, the chip's clock comes out between 0.5 and 3 GHz
-    clk = torch.zeros(2, dtype=torch.int64, device="cuda")
-    c2r.probe_mfma_bf16(ops, 20000, 256, torch.zeros(256 * 512, dtype=torch.float32, device="cuda"), clk)
-    torch.cuda.synchronize()
-    cyc, ticks = clk.tolist()
-    assert cyc >= 20000 * 8 * 4 and ticks > 0           # at least 4 cycles per matrix instruction
-    assert 0.5e9 < cyc / (ticks / 1e8) < 3.0e9
-
-
 @pytest.mark.parametrize("E,K,T,n_dev,holes", [(12, 4, 300, 4, True), (60, 4, 5000, 4, False), (64, 8, 1025, 64, True),
                                                (8, 2, 1, 2, False), (60, 4, 8192, 6, False), (16, 1, 4100, 3, True),
                                                # K > 8: the devices of a token no longer fit one packed register
@@ -472,28 +467,3 @@ def test_distinct_devices(c2r, orc, T, K, E, eps):
         ref = np.array([len({map2[e] for e in row if e >= 0 and map2[e] >= 0}) for row in idx2])
         tot2, pt2 = c2r.distinct_devices(dev(idx2), E, dev(map2), n_dev, per_token=True)
         assert np.array_equal(host(pt2)[0], ref) and int(host(tot2)[0]) == int(ref.sum())
-
-
-def test_launch_timer(c2r):
-    # the timer takes the next launch of the fast bf16 FFN kernel on this thread, and only that one
-    T, d, F = 512, 256, 128
-    x = torch.randn(T, d, device="cuda").to(torch.bfloat16)
-    wg = torch.randn(1, F, d, device="cuda").to(torch.bfloat16)
-    wu = torch.randn(1, F, d, device="cuda").to(torch.bfloat16)
-    off = torch.tensor([0, T], dtype=torch.int32, device="cuda")
-    h_plain = torch.empty(T, F, dtype=torch.bfloat16, device="cuda")
-    h_timed = torch.empty_like(h_plain)
-    c2r.expert_ffn_gate_up(x, off, wg, wu, h_plain)
-    tm = c2r.LaunchTimer()
-    with pytest.raises(c2r.C2RError):
-        tm.elapsed_ms()                      # never armed
-    tm.arm()
-    with pytest.raises(c2r.C2RError):
-        tm.elapsed_ms()                      # armed, nothing launched yet
-    c2r.expert_ffn_gate_up(x, off, wg, wu, h_timed)
-    ms = tm.elapsed_ms()
-    assert 0.0 < ms < 50.0
-    assert torch.equal(h_plain, h_timed)     # same kernel, same result
-    c2r.expert_ffn_gate_up(x, off, wg, wu, h_timed)     # not armed: an ordinary launch
-    torch.cuda.synchronize()
-    assert tm.elapsed_ms() == ms             # the timer still holds the launch it took
