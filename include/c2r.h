@@ -162,6 +162,23 @@ int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T,
                 void *stream);
 
 /*
+ * c2r_permute for callers that cannot allocate device memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, results and errors,
+ * but no workspace argument - the block histograms live in a 2 MiB static device array that
+ * the library holds on every GPU it runs on until the process ends.  The call allocates
+ * nothing and frees nothing.
+ * Limit: T*K <= 4194304 assignments; beyond it C2R_ERR_UNSUPPORTED (use c2r_permute).
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two
+ * streams, two host threads) race on it and must be serialised by the caller; calls on one
+ * stream, or on different GPUs, are safe.  Nothing in the array needs clearing between calls
+ * (each call overwrites the part it reads).
+ */
+int c2r_permute_noalloc(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T, int d, int E,
+                        int K, const int32_t *local_slot, int E_local, int32_t *counts,
+                        int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
+                        void *stream);
+
+/*
  * Grouped expert FFN (Sec. 3.1: every token is processed by each expert selected for it):
  * for each local expert e and each row r in [offsets[e], offsets[e+1]):
  *     y_perm[r] = W_down,e ( silu(W_gate,e x_perm[r]) * (W_up,e x_perm[r]) )

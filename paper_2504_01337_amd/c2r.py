@@ -22,7 +22,7 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
              -4: "C2R_ERR_LAUNCH"}
 
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
-           "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_expert_ffn",
+           "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_permute_noalloc", "c2r_expert_ffn",
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_gather", "c2r_expert_ffn_down",
            "c2r_combine",
            "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies",
@@ -56,6 +56,7 @@ def lib():
         L.c2r_route.argtypes = [vp, i32, vp, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         L.c2r_route_from_logits.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp]
         L.c2r_permute.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.c2r_permute_noalloc.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
         L.c2r_expert_ffn.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_expert_ffn_gate_up.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
         L.c2r_expert_ffn_gate_up_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
@@ -191,6 +192,19 @@ def permute(x, topk_idx, E, local_slot=None, E_local=None, ws=None, out=None, ro
                                             _ptr(counts), _ptr(offsets), _ptr(perm), _ptr(inv_perm), _ptr(x_perm),
                                             _ptr(ws), ws.numel(), _stream()))
     return counts, offsets, perm, inv_perm, x_perm
+
+
+def permute_noalloc(x, topk_idx, E, local_slot, E_local, out):
+    """c2r_permute without a workspace (static device scratch); the caller passes every output:
+    out = (counts, offsets, perm, inv_perm, x_perm or None).  Nothing is allocated."""
+    T, K = topk_idx.shape
+    counts, offsets, perm, inv_perm, x_perm = out
+    d = x.shape[1] if x is not None else 0
+    dt = _dt(x) if x is not None else F32
+    _check("c2r_permute_noalloc", lib().c2r_permute_noalloc(
+        _ptr(x), dt, _ptr(topk_idx), T, d, E, K, _ptr(local_slot), E_local, _ptr(counts), _ptr(offsets),
+        _ptr(perm), _ptr(inv_perm), _ptr(x_perm), _stream()))
+    return out
 
 
 def expert_ffn(x_perm, offsets, w_gate, w_up, w_down, ws=None, out=None):

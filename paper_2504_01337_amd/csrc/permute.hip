@@ -15,6 +15,8 @@
 // 32768 assignments and linear in their number; the three launches take 16-24 us from 65536 to
 // 262144 assignments).
 // Everything is deterministic: no atomically assigned slots.
+#include <mutex>
+
 #include "c2r_internal.h"
 
 namespace c2r {
@@ -304,10 +306,10 @@ size_t permute_workspace_bytes(int64_t T, int E, int K) {
 
 using namespace c2r;
 
-extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T, int d,
-                           int E, int K, const int32_t *local_slot, int E_local, int32_t *counts,
-                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
-                           void *ws, size_t ws_bytes, void *stream) {
+static int permute_impl(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T, int d,
+                        int E, int K, const int32_t *local_slot, int E_local, int32_t *counts,
+                        int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
+                        void *ws, size_t ws_bytes, void *stream) {
     drop_stale_error();
     if (T < 0 || E < 1 || K < 1 || E_local < 1 || E_local > E) return C2R_ERR_INVALID_ARG;
     if (!local_slot && E_local != E) return C2R_ERR_INVALID_ARG;
@@ -350,4 +352,52 @@ extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx,
         }
     }
     return launch_status();
+}
+
+extern "C" int c2r_permute(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T, int d,
+                           int E, int K, const int32_t *local_slot, int E_local, int32_t *counts,
+                           int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
+                           void *ws, size_t ws_bytes, void *stream) {
+    return permute_impl(x, dt, topk_idx, T, d, E, K, local_slot, E_local, counts, offsets, perm, inv_perm, x_perm,
+                        ws, ws_bytes, stream);
+}
+
+// ---- c2r_permute for callers that cannot allocate: the block histograms live in a static
+//      device array instead of a caller-provided workspace ----
+namespace c2r {
+constexpr int64_t NOALLOC_MAX_ASSIGNMENTS = 1ll << 22;
+constexpr size_t NOALLOC_SCRATCH_BYTES =
+    2 * (size_t)(NOALLOC_MAX_ASSIGNMENTS / PB_SPAN) * C2R_MAX_E * sizeof(int32_t);  // 2 MiB
+static __device__ __align__(256) unsigned char scratch[NOALLOC_SCRATCH_BYTES];
+constexpr int NOALLOC_MAX_DEVICES = 64;
+static void *scratch_ptr[NOALLOC_MAX_DEVICES];  // per device: every GPU holds its own copy of the array
+static std::mutex scratch_mutex;
+
+// Device address of the current device's copy of `scratch` (looked up once per device: in host
+// code the array's name is only a handle for this query, never an address a kernel may use).
+static int noalloc_scratch(void **out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= NOALLOC_MAX_DEVICES) return C2R_ERR_LAUNCH;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return C2R_ERR_LAUNCH;
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return C2R_OK;
+}
+}  // namespace c2r
+
+extern "C" int c2r_permute_noalloc(const void *x, c2r_dtype dt, const int32_t *topk_idx, int64_t T, int d,
+                                   int E, int K, const int32_t *local_slot, int E_local, int32_t *counts,
+                                   int32_t *offsets, int32_t *perm, int32_t *inv_perm, void *x_perm,
+                                   void *stream) {
+    if (T < 0 || K < 1) return C2R_ERR_INVALID_ARG;
+    if (T > NOALLOC_MAX_ASSIGNMENTS || T * (int64_t)K > NOALLOC_MAX_ASSIGNMENTS) return C2R_ERR_UNSUPPORTED;
+    void *ws = nullptr;
+    const int rc = noalloc_scratch(&ws);
+    if (rc != C2R_OK) return rc;
+    return permute_impl(x, dt, topk_idx, T, d, E, K, local_slot, E_local, counts, offsets, perm, inv_perm, x_perm,
+                        ws, NOALLOC_SCRATCH_BYTES, stream);
 }

@@ -84,6 +84,8 @@ def test_argument_errors_before_launch():
     assert L.c2r_distinct_devices(p, 16, 2, 8, p, 2, 4, null, null, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_distinct_devices(p, 16, 2, 8, p, 2, 4, null, ctypes.c_void_p(0x1004), null) == c2r.ERR_INVALID_ARG
     assert c2r.workspace_bytes(c2r.STAGE_DEDUP_DISPATCH, 5000, 0, 4, 4, 0, c2r.F32) == 256
+    # the allocation-free dispatch rejects what its static array cannot hold
+    assert L.c2r_permute_noalloc(p, 1, p, (1 << 20) + 1, 64, 8, 4, null, 8, p, p, p, p, p, null) == c2r.ERR_UNSUPPORTED
     # empty batches are fine and launch nothing
     assert L.c2r_route(null, 1, null, null, 0, 64, 8, 2, null, 0, null, null, null, null, 0, null) == c2r.OK
     assert L.c2r_combine(null, 1, null, null, 0, 64, 2, null, null, null) == c2r.OK
