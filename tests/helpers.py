@@ -32,7 +32,32 @@ def max_rel_err(got, ref):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300))
 
 
+# Relative tolerance of the fp32 gates against the oracle's fp64 gates (both from the same fp32
+# logits).  A gate is exp(a_s) / sum_s' exp(a_s') with a_s = l_s - l_0 <= 0.  In fp32: a_s is one
+# rounded subtraction (relative 2^-24, so exp(a_s) moves by |a_s| 2^-24 relatively), the exponential
+# is good to 2 ulp, the sum of K <= 8 positive terms to (K - 1) roundings, the division to 1 ulp:
+# (|a_s| + 2 + 7 + 1) 2^-24 in all.  A gate that is not flushed to zero has |a_s| < 88 in
+# principle, but the workloads' logits differ by less than 24 inside a token's kept set, which
+# gives (24 + 10) 2^-24 = 2.0e-6.  (1e-6 would hold only for |a_s| < 7.)
+GATE_RTOL = 2e-6
+
+
+def share_outside(got, ref, tol):
+    """Second error measure of the layer-output bar: the share of elements whose error exceeds
+    tol * (|ref| + rms(ref)), so that rows that are small next to the batch maximum count too."""
+    ref = np.asarray(ref, dtype=np.float64)
+    got = np.asarray(got, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    return float(np.mean(np.abs(got - ref) > tol * (np.abs(ref) + rms)))
+
+
 TOL = {"f32": 1e-5, "bf16": 1e-2}
+# Share of elements allowed outside tol * (|ref| + rms): none in fp32.  In bf16 every output is
+# rounded to 8 significant bits three times on the way (h, y_perm, y): an element's error is
+# a few times 2^-9 of the magnitude of the TERMS it sums, which for an element that is itself
+# near zero is a few times 2^-9 * rms, i.e. inside 1e-2 * rms but not by a wide margin, so a
+# small share of elements is allowed to land outside.
+SHARE_OUTSIDE_MAX = {"f32": 0.0, "bf16": 1e-3}
 
 
 class OracleLayer:

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2504_01337_amd import workloads as wl
-from helpers import OracleLayer, TOL, dev, host, max_rel_err
+from helpers import GATE_RTOL, OracleLayer, SHARE_OUTSIDE_MAX, TOL, dev, host, max_rel_err, share_outside
 
 pytestmark = pytest.mark.gpu
 
@@ -55,20 +55,31 @@ def _run_layer(c2r, orc, w, n_sample):
     else:
         x_perm_dev = layer.x_perm
     assert np.array_equal(host(layer.idx), o.idx)
-    np.testing.assert_allclose(host(layer.gates), o.gates, rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(host(layer.gates), o.gates, rtol=GATE_RTOL, atol=1e-7)
     assert np.array_equal(host(layer.counts), o.counts)
     assert np.array_equal(host(layer.offsets), o.offsets)
     n = int(o.offsets[-1])
     assert np.array_equal(host(layer.perm)[:n], o.perm)
     assert np.array_equal(host(layer.inv_perm), o.inv_perm)
     assert np.array_equal(host(x_perm_dev)[:n], o.x[o.perm // w.K])
-    # --- outputs on sampled tokens the oracle computes one by one ---
-    rng = np.random.default_rng(w.cfg_id)
-    toks = np.sort(rng.permutation(w.T)[:n_sample])
+    # --- outputs: every token of the batch (n_sample None) or sampled tokens, which the oracle
+    #     computes one by one; two measures: max |d| / max |ref| and the share of elements
+    #     with |d| > tol * (|ref| + rms(ref)) ---
+    if n_sample is None or n_sample >= w.T:
+        toks = np.arange(w.T)
+    else:
+        toks = np.sort(np.random.default_rng(w.cfg_id).permutation(w.T)[:n_sample])
     ref = orc.layer_tokens(o.x, toks, o.idx, o.gates, wg, wu, wd, w.E, o.local_slot, shared)
-    err = max_rel_err(host(y)[toks], ref)
-    print(f"[layer] {w.name} max rel err {err:.3e} (bar {TOL[w.dtype]})", flush=True)
+    got = host(y)[toks]
+    err = max_rel_err(got, ref)
+    share = share_outside(got, ref, TOL[w.dtype])
+    # the worst token (row) by its own scale, for the report
+    row_err = np.abs(got - ref).max(axis=1) / np.maximum(np.abs(ref).max(axis=1), 1e-30)
+    print(f"[layer] {w.name} {len(toks)} tokens: max rel err {err:.3e} (bar {TOL[w.dtype]}); share of elements "
+          f"outside tol*(|ref|+rms) {share:.2e} (bar {SHARE_OUTSIDE_MAX[w.dtype]}); worst row by its own "
+          f"max {np.nanmax(row_err):.3e}", flush=True)
     assert err <= TOL[w.dtype]
+    assert share <= SHARE_OUTSIDE_MAX[w.dtype]
     assert torch.isfinite(y.float()).all()
     layer.Cm = Cm
     return layer, o
@@ -87,7 +98,7 @@ def test_layer_reduced(c2r, orc, name, T, Tp):
 @pytest.mark.parametrize("name", ["C2", "C3", "C5"])
 def test_layer_full_size(c2r, orc, name):
     w = wl.WORKLOADS[name]
-    layer, o = _run_layer(c2r, orc, w, n_sample=48)
+    layer, o = _run_layer(c2r, orc, w, n_sample=None)    # every token of the batch
     if name in ("C3", "C5"):
         # Sec. 3.4 at full size: the zero-redundancy send list under a fixed 4-way contiguous map
         # (bit exact), its copy count against the host-side count of distinct devices, and the
@@ -136,7 +147,7 @@ def test_layer_llama_moe_shape_and_list_length_sweep(c2r, orc):
             idx, g, _ = c2r.route(x, Wg, bias, w.K, dev(ci))
             ri, rg = orc.route(o.logits, w.K, ci)
             assert np.array_equal(host(idx), ri), Tc
-            np.testing.assert_allclose(host(g), rg, rtol=2e-6, atol=1e-7)
+            np.testing.assert_allclose(host(g), rg, rtol=GATE_RTOL, atol=1e-7)
             if Tc == 1:                                    # Fig. 3, T = 1: the partner is the list entry
                 assert np.array_equal(ri[:, 1], ci[ri[:, 0], 0])
             if Tc == w.E - 1:                              # Fig. 3 caption: degenerates to top-K
@@ -158,7 +169,7 @@ def test_profiling_c4_full_size(c2r, orc):
     assert np.array_equal(host(Cm).astype(np.int64), C_ref)
     assert np.array_equal(host(collab), orc.collaborators(C_ref, w.Tc))
     sel = np.random.default_rng(4).permutation(w.T)[:4096]
-    np.testing.assert_allclose(host(gates)[sel], g_ref[sel], rtol=2e-6, atol=1e-7)
+    np.testing.assert_allclose(host(gates)[sel], g_ref[sel], rtol=GATE_RTOL, atol=1e-7)
 
 
 def test_layer_forward_in_a_captured_graph(c2r, orc):

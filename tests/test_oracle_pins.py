@@ -5,6 +5,7 @@ plausible slip in oracle/c2r_oracle.c (dropped term, wrong sign or index,
 transposed operand, wrong tie rule) fails it.
 """
 import itertools
+import math
 import os
 
 import numpy as np
@@ -497,3 +498,41 @@ def test_collaboration_degree_closed_forms(orc):
     for i in range(N):
         Cm[i, (i + 1) % N] = 5                  # one collaborator each: fully specialised
     assert np.all(orc.collaboration_degree(Cm) == 0)
+
+
+def test_collaboration_degree_hand_worked_rows(orc):
+    # Eq. 3 on rows that are neither uniform nor one-hot, worked by hand.  Expert 0 meets the
+    # others 2, 1 and 1 times: p = 1/2, 1/4, 1/4 and
+    #   P = (1/2) ln 2 + 2 (1/4) ln 4 = (3/2) ln 2.
+    # Expert 1 meets only expert 0: P = 0.  Experts 2 and 3 meet others 1 and 3 times:
+    #   p = 1/4, 3/4 and P = (1/4) ln 4 + (3/4) ln (4/3) = ln 4 - (3/4) ln 3.
+    # The large diagonal (an expert's own token count) must enter neither sum.
+    Cm = np.array([[100, 2, 1, 1],
+                   [2, 50, 0, 0],
+                   [1, 0, 7, 3],
+                   [1, 0, 3, 9]])
+    want = [1.5 * math.log(2.0), 0.0, math.log(4.0) - 0.75 * math.log(3.0), math.log(4.0) - 0.75 * math.log(3.0)]
+    np.testing.assert_allclose(orc.collaboration_degree(Cm), want, rtol=1e-15, atol=0)
+    # a mistake that keeps the diagonal in the normalisation gives a different, smaller number
+    assert abs(want[0] - 1.0397207708399179) < 1e-15
+
+
+def test_place_experts_hand_worked_pick_sequence(orc):
+    # Sec. 3.4 co-location (greedy reading) on a generic symmetric matrix, picks worked by hand.
+    # Off-diagonal row sums: 15, 13, 12, 13, 8, 13.  The diagonal (50 for expert 1) is ignored.
+    Cm = np.array([[1, 5, 1, 0, 2, 7],
+                   [5, 50, 3, 4, 0, 1],
+                   [1, 3, 1, 6, 2, 0],
+                   [0, 4, 6, 1, 1, 2],
+                   [2, 0, 2, 1, 1, 3],
+                   [7, 1, 0, 2, 3, 1]], dtype=np.int64)
+    assert np.array_equal(Cm, Cm.T)
+    # three devices of two: device 0 starts with expert 0 (row sum 15) and takes expert 5 (7 with 0);
+    # device 1 starts with expert 1 (row sums over ALL other experts: 13 ties with expert 3's 13,
+    # lower index wins) and takes expert 3 (4 with 1, against 3 for expert 2); experts 2, 4 remain.
+    assert list(orc.place_experts(Cm, 3)) == [0, 1, 2, 1, 2, 0]
+    # two devices of three: {0, 5} then the largest TOTAL with both: expert 1 (5 + 1 = 6) against
+    # expert 4 (2 + 3 = 5), expert 3 (0 + 2) and expert 2 (1 + 0)
+    assert list(orc.place_experts(Cm, 2)) == [0, 0, 1, 1, 1, 0]
+    # six devices of one: descending row sum, ties to the lower index: 0, then 1, 3, 5 (13 each), 2, 4
+    assert list(orc.place_experts(Cm, 6)) == [0, 1, 4, 2, 5, 3]
