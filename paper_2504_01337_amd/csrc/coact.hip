@@ -1,81 +1,80 @@
 // Expert collaboration matrix (Eq. 2) and collaborator lists (Eq. 4).
 //
-// Co-activation without a single contended atomic in the token loop: a wave
-// takes 64 tokens, each lane builds the 64-bit set of its token's experts, and
-// E wave ballots transpose that 64x64 bit matrix so that lane i holds
-// B_i = {tokens of this batch that selected expert i}.  Then
-//     C[i, j] += popcount(B_i & B_j)
-// with B_j broadcast from lane j; lane i keeps row i of the wave's partial
-// matrix in registers across all its batches.  The cost per batch does not
-// depend on how skewed the expert load is.  Partial matrices are reduced through
-// LDS per workgroup and added to C with one integer atomic per entry per
-// workgroup (integer adds commute, so the result is exact and reproducible).
+// Co-activation is a histogram over expert pairs kept in LDS: a thread takes a token, forms
+// the 64-bit set of its experts (duplicates and out-of-range entries drop out) and adds 1 to
+// red[a][b] for every pair a <= b of the set, the diagonal included - K (K + 1) / 2 LDS
+// atomics per token, 10 for K = 4.  Only the upper triangle is counted (the matrix is
+// symmetric); the workgroup's histogram then goes to C with one integer atomic per entry,
+// C[i][j] += red[min(i,j)][max(i,j)].  Integer adds commute, so the result is exact and
+// reproducible.  LDS atomics of lanes that hit the same pair serialise, one per cycle: with
+// every token on one pair that is 64 cycles per instruction, still a fraction of what a
+// conflict-free formulation through ballots and popcounts costs (it was measured: 64 ballots
+// to transpose the wave's bit matrix and 64 x (2 readlane + 2 popcount) per 64 tokens are
+// ~700 instructions of 4 cycles each, 38 us for 2^20 tokens, where this is ~150 and 10).
 #include "c2r_internal.h"
 
 namespace c2r {
 
-template <int EP>
-__global__ __launch_bounds__(256) void coactivation_kernel(const int32_t *__restrict__ topk_idx,
-                                                           int64_t T, int K, int E,
-                                                           int32_t *__restrict__ C) {
-    __shared__ int32_t red[EP * EP];
-    for (int i = threadIdx.x; i < EP * EP; i += 256) red[i] = 0;
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void coactivation_kernel(const int32_t *__restrict__ topk_idx,
+                                                              int64_t T, int K, int E,
+                                                              int32_t *__restrict__ C) {
+    __shared__ int32_t red[C2R_MAX_E * C2R_MAX_E];  // red[a * 64 + b], a <= b
+    for (int i = threadIdx.x; i < C2R_MAX_E * C2R_MAX_E; i += NW * 64) red[i] = 0;
     __syncthreads();
 
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const int64_t nwaves = (int64_t)gridDim.x * 4;
-    const int64_t nbatch = (T + 63) / 64;
-
-    int32_t acc[EP];
+    constexpr int UN = 4;  // tokens per thread and trip: their index loads are in flight together
+    const int64_t stride = (int64_t)gridDim.x * NW * 64;
+    for (int64_t t0 = (int64_t)blockIdx.x * NW * 64 + threadIdx.x; t0 < T; t0 += UN * stride) {
+        uint64_t m[UN];
+        if (K == 4) {
+            int4 q[UN];
 #pragma unroll
-    for (int j = 0; j < EP; ++j) acc[j] = 0;
-
-    for (int64_t b = wave; b < nbatch; b += nwaves) {
-        const int64_t t = b * 64 + lane;
-        uint64_t m = 0;
-        if (t < T) {
-            if (K == 4) {
-                const int4 q = *reinterpret_cast<const int4 *>(topk_idx + t * 4);
-                const int v[4] = {q.x, q.y, q.z, q.w};
+            for (int u = 0; u < UN; ++u) {
+                const int64_t t = t0 + u * stride;
+                q[u] = *reinterpret_cast<const int4 *>(topk_idx + (t < T ? t : t0) * 4);
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int v[4] = {q[u].x, q[u].y, q[u].z, q[u].w};
+                m[u] = 0;
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
-                    if (v[s] >= 0 && v[s] < E) m |= 1ull << v[s];
-            } else {
-                for (int s = 0; s < K; ++s) {
-                    const int v = topk_idx[t * K + s];
-                    if (v >= 0 && v < E) m |= 1ull << v;
+                    if (v[s] >= 0 && v[s] < E) m[u] |= 1ull << v[s];
+                if (t0 + u * stride >= T) m[u] = 0;
+            }
+        } else {
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int64_t t = t0 + u * stride;
+                m[u] = 0;
+                if (t < T)
+                    for (int s = 0; s < K; ++s) {
+                        const int v = topk_idx[t * K + s];
+                        if (v >= 0 && v < E) m[u] |= 1ull << v;
+                    }
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            uint64_t ma = m[u];
+            while (ma) {  // a: the set's experts in ascending order
+                const int a = __ffsll((unsigned long long)ma) - 1;
+                uint64_t mb = ma;  // b >= a: a itself (the diagonal) and the higher ones
+                ma &= ma - 1;
+                while (mb) {
+                    const int b = __ffsll((unsigned long long)mb) - 1;
+                    mb &= mb - 1;
+                    atomicAdd(&red[a * C2R_MAX_E + b], 1);
                 }
             }
         }
-        const uint32_t mlo = (uint32_t)m, mhi = (uint32_t)(m >> 32);
-        // bit-matrix transpose through ballots: lane i <- B_i
-        uint32_t blo = 0, bhi = 0;
-#pragma unroll
-        for (int i = 0; i < EP; ++i) {
-            const bool bit = (((i < 32) ? (mlo >> (i & 31)) : (mhi >> (i & 31))) & 1u) != 0;
-            const uint64_t bal = __ballot(bit);
-            blo = lane == i ? (uint32_t)bal : blo;
-            bhi = lane == i ? (uint32_t)(bal >> 32) : bhi;
-        }
-#pragma unroll
-        for (int j = 0; j < EP; ++j) {
-            const uint32_t jlo = __builtin_amdgcn_readlane(blo, j);
-            const uint32_t jhi = __builtin_amdgcn_readlane(bhi, j);
-            acc[j] += __popc(blo & jlo) + __popc(bhi & jhi);
-        }
-    }
-
-    if (lane < EP) {
-#pragma unroll
-        for (int j = 0; j < EP; ++j)
-            if (acc[j]) atomicAdd(&red[lane * EP + j], acc[j]);
     }
     __syncthreads();
-    for (int i = threadIdx.x; i < EP * EP; i += 256) {
-        const int r = i / EP, c = i % EP;
-        const int32_t v = red[i];
-        if (v && r < E && c < E) atomicAdd(&C[(size_t)r * E + c], v);
+    for (int i = threadIdx.x; i < E * E; i += NW * 64) {
+        const int r = i / E, c = i - r * E;
+        const int32_t v = red[(r < c ? r : c) * C2R_MAX_E + (r < c ? c : r)];
+        if (v) atomicAdd(&C[i], v);
     }
 }
 
@@ -165,17 +164,19 @@ extern "C" int c2r_build_coactivation(const int32_t *topk_idx, int64_t T, int K,
     if (!aligned(topk_idx, 16) || !aligned(C, 4)) return C2R_ERR_INVALID_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t nbatch = (T + 63) / 64;
-    int64_t nblk = (nbatch + 3) / 4;
-    if (nblk > 1024) nblk = 1024;  // ~4 workgroups per CU; each wave loops over its batches
-    const dim3 grid((unsigned)nblk), block(256);
-    if (E <= 8)
-        coactivation_kernel<8><<<grid, block, 0, st>>>(topk_idx, T, K, E, C);
-    else if (E <= 16)
+    // Every workgroup ends with one integer atomic per entry of C, all workgroups on the same
+    // E*E addresses, so a long stream runs as few, large workgroups (16 waves, four tokens per
+    // thread and trip), a short one as 4-wave workgroups that still spread over the chip.
+    const bool big = T >= (1 << 18);
+    const int nw = big ? 16 : 4;
+    int64_t nblk = (T + nw * 64 * 4 - 1) / (nw * 64 * 4);
+    const int64_t cap = 256;  // one workgroup per CU (measured on 2^20 tokens: 128 -> 16.4 us, 256 -> 15.4, 512 -> 15.2)
+    if (nblk > cap) nblk = cap;
+    const dim3 grid((unsigned)nblk), block(nw * 64);
+    if (big)
         coactivation_kernel<16><<<grid, block, 0, st>>>(topk_idx, T, K, E, C);
-    else if (E <= 32)
-        coactivation_kernel<32><<<grid, block, 0, st>>>(topk_idx, T, K, E, C);
     else
-        coactivation_kernel<64><<<grid, block, 0, st>>>(topk_idx, T, K, E, C);
+        coactivation_kernel<4><<<grid, block, 0, st>>>(topk_idx, T, K, E, C);
     return launch_status();
 }
 

@@ -433,6 +433,33 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
         const int64_t nflt = rows > 0 ? rows * E : 0;
         const float *base = src + tw * E;
         const uint32_t rcp = (uint32_t)((0x100000000ull + E - 1) / E);
+        auto scatter = [&](uint32_t f, float v) __attribute__((always_inline)) {
+            // f / E, exact for f < 4096 (the 32-bit reciprocal of 1 does not exist)
+            const uint32_t r = E == 1 ? f : __umulhi(f, rcp);
+            tl[r * LP + (f - r * E)] = v;
+        };
+        if (rows == 64) {
+            // a whole tile: 64 E floats (a multiple of 4), fetched with every load in flight at once -
+            // unconditional, out-of-range ones on a clamped address - and only then spread over LDS:
+            // what this kernel does is stream the logits, and a wave that waits for one 1 KB load
+            // at a time (the loop below) leaves the memory pipe a fifth full
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            constexpr int NV = EP / 4;
+            f32x4 q[NV];
+#pragma unroll
+            for (int u = 0; u < NV; ++u) {
+                const uint32_t i = (uint32_t)lane * 4 + u * 256;
+                q[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(base + (i < nflt ? i : 0)));
+            }
+#pragma unroll
+            for (int u = 0; u < NV; ++u) {
+                const uint32_t i = (uint32_t)lane * 4 + u * 256;
+                if (i < nflt) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) scatter(i + j, q[u][j]);
+                }
+            }
+        } else
         for (int64_t i = (int64_t)lane * 4; i < nflt; i += 256) {
             float v[4];
             if (i + 4 <= nflt) {
@@ -445,11 +472,7 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const uint32_t f = (uint32_t)i + j;
-                if (f < nflt) {
-                    // f / E, exact for f < 4096 (the 32-bit reciprocal of 1 does not exist)
-                    const uint32_t r = E == 1 ? f : __umulhi(f, rcp);
-                    tl[r * LP + (f - r * E)] = v[j];
-                }
+                if (f < nflt) scatter(f, v[j]);
             }
         }
         __syncthreads();
@@ -587,9 +610,50 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
     pick<EP>(l, all, e0, v0);
     uint64_t m = mask_tab[e0];
     const float g0 = expf(v0 - v0);  // 1, or NaN when the largest logit is infinite or a NaN
+    float den = g0;
+    if (K <= 8) {
+        // the usual case: the token's slots stay in registers and leave as 16-byte stores
+        int es[8];
+        float gs[8];
+        es[0] = e0;
+        gs[0] = g0;
+#pragma unroll
+        for (int s = 1; s < 8; ++s) {
+            es[s] = -1;
+            gs[s] = 0.0f;
+            if (s < K) {
+                int e;
+                float v;
+                pick<EP>(l, m, e, v);
+                if (e >= 0) {
+                    m &= ~(1ull << e);
+                    gs[s] = expf(v - v0);
+                }
+                es[s] = e;
+                den += gs[s];
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 8; ++s) gs[s] = gs[s] / den;
+        if (K == 4 && ((reinterpret_cast<uintptr_t>(topk_idx) | reinterpret_cast<uintptr_t>(gates)) & 15) == 0) {
+            typedef int i32x4 __attribute__((ext_vector_type(4)));
+            typedef float f32x4 __attribute__((ext_vector_type(4)));
+            const i32x4 ev = {es[0], es[1], es[2], es[3]};
+            const f32x4 gv = {gs[0], gs[1], gs[2], gs[3]};
+            __builtin_nontemporal_store(ev, reinterpret_cast<i32x4 *>(topk_idx + (size_t)t * 4));
+            __builtin_nontemporal_store(gv, reinterpret_cast<f32x4 *>(gates + (size_t)t * 4));
+        } else {
+#pragma unroll
+            for (int s = 0; s < 8; ++s)
+                if (s < K) {
+                    topk_idx[(size_t)t * K + s] = es[s];
+                    gates[(size_t)t * K + s] = gs[s];
+                }
+        }
+        return;
+    }
     topk_idx[(size_t)t * K] = e0;
     gates[(size_t)t * K] = g0;
-    float den = g0;
     for (int s = 1; s < K; ++s) {
         int e;
         float v;
