@@ -251,6 +251,8 @@ def main():
                     help="C1|C2|C3|C5 (C3 = Qwen1.5-MoE-A2.7B-shaped layer) or C4 (profiling only: stored "
                          "logits -> top-K -> co-activation matrix -> collaborator lists)")
     ap.add_argument("--cpu-sample", type=int, default=8192, help="tokens the CPU oracle is timed on (0: skip)")
+    ap.add_argument("--separate-shared", action="store_true",
+                    help="launch the shared expert's FFN passes on their own (four FFN launches per step instead of two)")
     ap.add_argument("--overlap", action="store_true",
                     help="run the shared expert on a second stream (stage spans then overlap)")
     ap.add_argument("--no-isolate", dest="isolate", action="store_false",
@@ -317,11 +319,13 @@ def main():
     t_gen = time.time() - t_gen
 
     L = c2r.C2RLayer(w.T, w.d, w.E, w.K, w.F, tdt, Wg, bias, collab, *wgt,
-                     local_slot=dev(ls_h), E_local=w.n_local, shared=shared, overlap=args.overlap)
+                     local_slot=dev(ls_h), E_local=w.n_local, shared=shared, overlap=args.overlap,
+                     fuse_shared=False if args.separate_shared else None)
     # One step = one forward of the layer as the product enqueues it (C2RLayer.forward).
     # Each stage's start/end events are recorded on the stream the stage runs on; with
     # --overlap the spans of stages that run side by side overlap.
-    stages = [s for s in L.STAGES if shared or not s.startswith("shared")]
+    stages = list(L.stage_names())
+    sep_shared = bool(shared) and not L.fuse_shared      # the shared expert has launches of its own
     dom_stages = [s for s in ("ffn_gate_up", "shared_gate_up") if s in stages]   # launches of the dominant kernel
     mk = lambda: torch.cuda.Event(enable_timing=True)
     # timed region: only the dominant kernel's launches carry events, and only on every fourth
@@ -359,9 +363,9 @@ def main():
     torch.cuda.synchronize()
     st_ms = {s: float(np.mean([ev[i][s][0].elapsed_time(ev[i][s][1]) for i in range(args.steps)])) for s in stages}
     # all four FFN launches: from the first one's start to the last one's end
-    first = "shared_gate_up" if shared else "ffn_gate_up"
+    first = "shared_gate_up" if sep_shared else "ffn_gate_up"
     ffn_span_ms = float(np.mean([max(ev[i][first][0].elapsed_time(ev[i]["ffn_down"][1]),
-                                     ev[i][first][0].elapsed_time(ev[i]["shared_down"][1]) if shared else 0.0)
+                                     ev[i][first][0].elapsed_time(ev[i]["shared_down"][1]) if sep_shared else 0.0)
                                  for i in range(args.steps)]))
 
     # the ABI's stand-alone dispatch (index sort + row gather into x_perm), timed outside the step
@@ -471,9 +475,11 @@ def main():
     fl_dn = 2.0 * n_local * w.d * w.F
     fl_sgu = 4.0 * w.T * w.d * w.F_shared
     fl_sdn = 2.0 * w.T * w.d * w.F_shared
+    if shared and L.fuse_shared:     # one launch per pass carries the routed groups and the shared expert
+        fl_gu, fl_dn, fl_sgu, fl_sdn = fl_gu + fl_sgu, fl_dn + fl_sdn, 0.0, 0.0
     # a layer that cannot fold the gather into the first pass (or split the shared expert) runs both
     # passes of that FFN in one call, inside the span of its "gate_up" stage: report them as one
-    both = {"ffn_gate_up": not L.fuse_gather, "shared_gate_up": shared and not L.split_shared}
+    both = {"ffn_gate_up": not L.fuse_gather, "shared_gate_up": sep_shared and not L.split_shared}
     for name, fl, fl2, second in (("ffn_gate_up", fl_gu, fl_dn, "ffn_down"), ("shared_gate_up", fl_sgu, fl_sdn, "shared_down")):
         if fl <= 0:
             continue
@@ -496,6 +502,9 @@ def main():
     nz = cnts > 0
     t_gu = np.maximum(4.0 * cnts * w.d * w.F / peak_fl, (2.0 * w.F * w.d + cnts * (w.d + w.F)) * sz / hbm)[nz].sum()
     t_dn = np.maximum(2.0 * cnts * w.d * w.F / peak_fl, (1.0 * w.F * w.d + cnts * (w.d + w.F)) * sz / hbm)[nz].sum()
+    if shared and L.fuse_shared:     # the shared expert is one more group of the same launch
+        t_gu += max(4.0 * w.T * w.d * w.F_shared / peak_fl, (2.0 * w.F_shared * w.d + w.T * (w.d + w.F_shared)) * sz / hbm)
+        t_dn += max(2.0 * w.T * w.d * w.F_shared / peak_fl, (1.0 * w.F_shared * w.d + w.T * (w.d + w.F_shared)) * sz / hbm)
     for name, t in (("ffn_gate_up", t_gu), ("ffn_down", t_dn)):
         if name in stage_info:
             stage_info[name]["groupwise_roof_ms"] = t * 1e3
@@ -505,7 +514,7 @@ def main():
     ffn_tf = (fl_gu + fl_dn + fl_sgu + fl_sdn) / ffn_span_ms / 1e9
     stage_info["expert_ffn_all"] = {"ms": ffn_span_ms, "TFLOPs": ffn_tf, "frac_mfma": ffn_tf / PEAK["mfma_bf16_TFLOPs"],
                                     "note": "first FFN launch's start to last one's end; route and permute run inside it"
-                                            if L.overlap else "sum of the four launches"}
+                                            if L.overlap else "sum of the FFN launches"}
 
     # HBM traffic of the dominant kernel per launch, from the committed rocprofv3 --pmc summary (if any)
     traffic, traffic_src = None, None
@@ -518,7 +527,7 @@ def main():
                 traffic_src = f"profiles/{os.path.basename(tfile)} (counters of a separate rocprofv3 --pmc run, " \
                               f"library at commit {line.split(':')[1].strip()})"
     # dominant kernel: the gate/up pass (launched for the routed groups and, if any, the shared expert)
-    n_launch = 2 if shared else 1
+    n_launch = 2 if sep_shared else 1
     dom_ms = sum(dom_ms_live.values()) / n_launch   # from the timed region
     dom_fl = (fl_gu + fl_sgu) / n_launch
     both = ""
@@ -526,7 +535,7 @@ def main():
     # two passes are not bracketed separately: the events then span both kernels of a call
     if not L.fuse_gather:
         dom_fl += fl_dn / n_launch
-    if shared and not L.split_shared:
+    if sep_shared and not L.split_shared:
         dom_fl += fl_sdn / n_launch
     if not L.fuse_gather:
         both = " and <1> (both passes of c2r_expert_ffn)"
@@ -534,7 +543,9 @@ def main():
             if k_gu in stage_info and k_dn in stage_info:
                 stage_info[k_gu]["note"] = "both passes (c2r_expert_ffn); flops of gate/up only in TFLOPs"
     if w.dtype == "bf16":
-        roofline = {"kernel": "ffn_bf16_dma_kernel<0>" + both + " (gate/up + SwiGLU)", "bound": "mfma",
+        roofline = {"kernel": "ffn_bf16_dma_kernel<0>" + both + " (gate/up + SwiGLU" +
+                              ("; routed groups and shared expert in one launch)" if shared and L.fuse_shared else ")"),
+                    "bound": "mfma",
                     "achieved": dom_fl / dom_ms / 1e9, "peak": PEAK["mfma_bf16_TFLOPs"], "unit": "TFLOP/s",
                     "frac": dom_fl / dom_ms / 1e9 / PEAK["mfma_bf16_TFLOPs"], "traffic": traffic,
                     "traffic_source": traffic_src,
@@ -625,7 +636,8 @@ def main():
         "measured_ceilings": ceilings, "zero_redundancy_dispatch": zr,
         "schedule": ("two streams: shared gate/up beside route+permute, routed gate/up alone, the two down passes "
                      "side by side; stage times are spans on their own stream and overlap") if L.overlap
-                    else "one stream, stages back to back",
+                    else "one stream, stages back to back" + ("; each FFN pass is one launch over the routed groups and "
+                                                              "the shared expert" if shared and L.fuse_shared else ""),
         "setup_s": t_gen,
     }
     if isolated is not None:

@@ -237,6 +237,31 @@ int c2r_expert_ffn_gather(const void *x, c2r_dtype dt, const int32_t *perm, int6
                           void *ws, size_t ws_bytes, void *stream);
 
 /*
+ * The two FFN passes for a layer that also has an always-on shared expert (the Qwen1.5-MoE
+ * setting of Sec. 4.1: routed experts plus one shared expert that every token runs through,
+ * Sec. 3.1 for the routed part): the routed groups AND the shared expert in ONE launch per
+ * pass, so that the shared expert's uniform tiles fill the compute units that the ragged
+ * groups' last tiles leave idle.  Results are bit-identical to
+ * c2r_expert_ffn_gate_up_gather / c2r_expert_ffn_down on the routed groups plus
+ * c2r_expert_ffn_gate_up / c2r_expert_ffn_down with E_local = 1, offsets = {0, T} on x.
+ *   gate_up : h[r, f]        = silu(W_gate,e[f,:] . x[perm[r] / K]) * (W_up,e[f,:] . x[perm[r] / K])
+ *             h_shared[t, f] = silu(Ws_gate[f,:] . x[t]) * (Ws_up[f,:] . x[t])
+ *   down    : y_perm[r, j]   = W_down,e[j,:] . h[r];   y_shared[t, j] = Ws_down[j,:] . h_shared[t]
+ * x : [T, d];  perm, offsets : as written by c2r_permute;  h : [A_cap, F];  y_perm : [A_cap, d]
+ * ws_gate, ws_up : [F_shared, d];  ws_down : [d, F_shared];  h_shared : [T, F_shared];
+ * y_shared : [T, d].  A_cap == 0 runs the shared expert alone.
+ * Limits: bf16; d, F and F_shared multiples of 64; T*d*2 < 2^32; else C2R_ERR_UNSUPPORTED.
+ */
+int c2r_expert_ffn_gate_up_with_shared(const void *x, c2r_dtype dt, const int32_t *perm, int64_t T, int K,
+                                       const int32_t *offsets, int E_local, int64_t A_cap, int d, int F,
+                                       const void *w_gate, const void *w_up, void *h, int F_shared,
+                                       const void *ws_gate, const void *ws_up, void *h_shared, void *stream);
+int c2r_expert_ffn_down_with_shared(const void *h, c2r_dtype dt, const int32_t *offsets, int E_local,
+                                    int64_t A_cap, int d, int F, const void *w_down, void *y_perm, int64_t T,
+                                    int F_shared, const void *h_shared, const void *ws_down, void *y_shared,
+                                    void *stream);
+
+/*
  * Un-permute and gate-weighted sum (Sec. 3.1, last sentence):
  *     y[t] = sum_{s<K, inv_perm[t*K+s] >= 0} gates[t,s] * y_perm[inv_perm[t*K+s]]  (+ y_shared[t])
  * summed in fp32 in slot order and rounded once to dt.

@@ -24,7 +24,7 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
            "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_permute_noalloc", "c2r_expert_ffn",
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_gather", "c2r_expert_ffn_down",
-           "c2r_combine",
+           "c2r_expert_ffn_gate_up_with_shared", "c2r_expert_ffn_down_with_shared", "c2r_combine",
            "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies",
            "c2r_collaboration_degree", "c2r_distinct_devices"]
 
@@ -62,6 +62,9 @@ def lib():
         L.c2r_expert_ffn_gate_up_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp]
         L.c2r_expert_ffn_gather.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_expert_ffn_down.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp]
+        L.c2r_expert_ffn_gate_up_with_shared.argtypes = [vp, i32, vp, i64, i32, vp, i32, i64, i32, i32, vp, vp, vp,
+                                                         i32, vp, vp, vp, vp]
+        L.c2r_expert_ffn_down_with_shared.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, i64, i32, vp, vp, vp, vp]
         L.c2r_combine.argtypes = [vp, i32, vp, vp, i64, i32, i32, vp, vp, vp]
         L.c2r_place_experts.argtypes = [vp, i32, i32, vp, vp]
         L.c2r_dedup_dispatch.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -273,6 +276,32 @@ def expert_ffn_down(h, offsets, w_down, y_perm):
     return y_perm
 
 
+def expert_ffn_gate_up_with_shared(x, perm, K, offsets, w_gate, w_up, h, ws_gate, ws_up, h_shared):
+    """First FFN pass of the routed groups (rows read through perm) and of the shared expert, one launch."""
+    T, d = x.shape
+    A_cap = perm.numel()
+    E_local, F, _ = w_gate.shape
+    Fs = ws_gate.shape[-2]
+    assert h.shape == (A_cap, F) and h_shared.shape == (T, Fs) and perm.dtype == torch.int32
+    assert ws_gate.shape[-1] == d and ws_up.shape[-2:] == (Fs, d)
+    _check("c2r_expert_ffn_gate_up_with_shared", lib().c2r_expert_ffn_gate_up_with_shared(
+        _ptr(x), _dt(x), _ptr(perm), T, K, _ptr(offsets), E_local, A_cap, d, F, _ptr(w_gate), _ptr(w_up), _ptr(h),
+        Fs, _ptr(ws_gate), _ptr(ws_up), _ptr(h_shared), _stream()))
+    return h, h_shared
+
+
+def expert_ffn_down_with_shared(h, offsets, w_down, y_perm, h_shared, ws_down, y_shared):
+    """Second FFN pass of the routed groups and of the shared expert, one launch."""
+    A_cap, F = h.shape
+    E_local, d, _ = w_down.shape
+    T, Fs = h_shared.shape
+    assert y_perm.shape == (A_cap, d) and y_shared.shape == (T, d) and ws_down.shape[-2:] == (d, Fs)
+    _check("c2r_expert_ffn_down_with_shared", lib().c2r_expert_ffn_down_with_shared(
+        _ptr(h), _dt(h), _ptr(offsets), E_local, A_cap, d, F, _ptr(w_down), _ptr(y_perm), T, Fs, _ptr(h_shared),
+        _ptr(ws_down), _ptr(y_shared), _stream()))
+    return y_perm, y_shared
+
+
 def combine(y_perm, gates, inv_perm, y_shared=None, out=None):
     """Un-permute + gate-weighted sum.  Returns y[T, d]."""
     T, K = gates.shape
@@ -364,7 +393,8 @@ class C2RLayer:
     beside them loses again).  The default is one stream: kernels that run alone can be timed."""
 
     def __init__(self, T, d, E, K, F, dtype, Wg, bias, collab_idx, w_gate, w_up, w_down,
-                 local_slot=None, E_local=None, shared=None, device="cuda", fuse_gather=None, overlap=False):
+                 local_slot=None, E_local=None, shared=None, device="cuda", fuse_gather=None, overlap=False,
+                 fuse_shared=None):
         self.T, self.d, self.E, self.K, self.F = T, d, E, K, F
         self.E_local = E if E_local is None else E_local
         self.Wg, self.bias, self.collab_idx = Wg, bias, collab_idx
@@ -409,12 +439,25 @@ class C2RLayer:
             self.y_shared = torch.empty((T, d), dtype=dtype, device=dev)
         else:
             self.y_shared = None
+        # routed groups and shared expert in ONE launch per FFN pass (c2r_expert_ffn_*_with_shared):
+        # the shared expert's uniform tiles fill the compute units that the ragged groups' last
+        # tiles leave idle.  Needs the split, gather-fused form of both and a single stream.
+        can_fuse_shared = (shared is not None and self.fuse_gather and self.split_shared and not self.overlap
+                           and T * d * 2 < (1 << 32))
+        self.fuse_shared = can_fuse_shared if fuse_shared is None else (bool(fuse_shared) and can_fuse_shared)
         if self.overlap:
             self.side = torch.cuda.Stream(device=dev)          # default priority
             self.ev = {k: torch.cuda.Event() for k in ("x", "shared_gate_up", "gate_up", "shared_down")}
 
-    # names of the stages forward() runs, in the order a trace lists them
+    # names of the stages forward() may run, in the order a trace lists them
     STAGES = ("route", "permute", "ffn_gate_up", "ffn_down", "shared_gate_up", "shared_down", "combine")
+
+    def stage_names(self):
+        """The stages this layer's forward() runs (with fuse_shared the shared expert is part of
+        ffn_gate_up and ffn_down)."""
+        if self.shared is None or self.fuse_shared:
+            return tuple(s for s in self.STAGES if not s.startswith("shared"))
+        return self.STAGES
 
     def forward(self, x, trace=None, only=None):
         """y = layer(x).  trace: optional {stage: (start_event, end_event)} for any subset of
@@ -436,7 +479,10 @@ class C2RLayer:
                     pair[1].record(stream)
 
         def gate_up():
-            if self.fuse_gather:
+            if self.fuse_shared:
+                expert_ffn_gate_up_with_shared(x, self.perm, self.K, self.offsets, self.w[0], self.w[1], self.h,
+                                               self.shared[0], self.shared[1], self.h_shared)
+            elif self.fuse_gather:
                 expert_ffn_gate_up_gather(x, self.perm, self.K, self.offsets, self.w[0], self.w[1], self.h)
             elif self.gather_both:   # both passes, rows read through perm
                 expert_ffn_gather(x, self.perm, self.K, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
@@ -444,7 +490,10 @@ class C2RLayer:
                 expert_ffn(self.x_perm, self.offsets, *self.w, ws=self.ws_ffn, out=self.y_perm)
 
         def down():
-            if self.fuse_gather:
+            if self.fuse_shared:
+                expert_ffn_down_with_shared(self.h, self.offsets, self.w[2], self.y_perm, self.h_shared,
+                                            self.shared[2], self.y_shared)
+            elif self.fuse_gather:
                 expert_ffn_down(self.h, self.offsets, self.w[2], self.y_perm)
 
         def shared_gate_up():
@@ -460,7 +509,7 @@ class C2RLayer:
         if self.overlap:
             self.ev["x"].record(main)                # x is ready, the previous call's combine has read y_shared
             side.wait_event(self.ev["x"])
-        if self.shared is not None:
+        if self.shared is not None and not self.fuse_shared:
             run("shared_gate_up", side, shared_gate_up)
             if self.overlap:
                 self.ev["shared_gate_up"].record(side)
@@ -474,7 +523,7 @@ class C2RLayer:
         if self.overlap:
             self.ev["gate_up"].record(main)
             side.wait_event(self.ev["gate_up"])
-        if self.shared is not None:
+        if self.shared is not None and not self.fuse_shared:
             run("shared_down", side, shared_down)
             if self.overlap:
                 self.ev["shared_down"].record(side)

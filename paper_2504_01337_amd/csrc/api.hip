@@ -14,6 +14,14 @@ int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t
                              int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1,
                              uint16_t *out, int ldo, const int32_t *gather, int gather_div, int gather_rows,
                              hipStream_t st);
+struct FfnProblem;
+}  // namespace c2r
+#include "ffn_common.h"
+namespace c2r {
+FfnProblem ffn_bf16_dma_problem(int pass, const uint16_t *a, int lda, const int32_t *offsets, int E_local,
+                                int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out,
+                                int ldo, const int32_t *gather, int gather_div, int gather_rows);
+int launch_ffn_bf16_dma(int pass, const FfnProblem &first, const FfnProblem *second, hipStream_t st);
 }  // namespace c2r
 
 using namespace c2r;
@@ -164,4 +172,65 @@ extern "C" int c2r_expert_ffn_gather(const void *x, c2r_dtype dt, const int32_t 
                                   static_cast<uint16_t *>(ws), ldh, perm, K, (int)T, static_cast<hipStream_t>(stream));
     if (rc != C2R_OK) return rc;
     return ffn_pass(1, dt, ws, offsets, E_local, A_cap, d, F, ldh, w_down, nullptr, y_perm, stream);
+}
+
+// ---- routed groups and an always-on shared expert in ONE launch per pass ----
+static int check_with_shared(c2r_dtype dt, int64_t T, int E_local, int64_t A_cap, int d, int F, int F_shared) {
+    int rc = check_ffn(dt, E_local, A_cap, d, F);
+    if (rc != C2R_OK) return rc;
+    if (T < 1 || F_shared < 1) return C2R_ERR_INVALID_ARG;
+    rc = check_ffn(dt, 1, T, d, F_shared);
+    if (rc != C2R_OK) return rc;
+    if (dt != C2R_BF16 || d % 64 != 0 || F % 64 != 0 || F_shared % 64 != 0) return C2R_ERR_UNSUPPORTED;
+    if ((uint64_t)T * d * 2 >= (1ull << 32)) return C2R_ERR_UNSUPPORTED;
+    return C2R_OK;
+}
+
+extern "C" int c2r_expert_ffn_gate_up_with_shared(const void *x, c2r_dtype dt, const int32_t *perm, int64_t T, int K,
+                                                  const int32_t *offsets, int E_local, int64_t A_cap, int d, int F,
+                                                  const void *w_gate, const void *w_up, void *h, int F_shared,
+                                                  const void *ws_gate, const void *ws_up, void *h_shared,
+                                                  void *stream) {
+    const int rc = check_with_shared(dt, T, E_local, A_cap, d, F, F_shared);
+    if (rc != C2R_OK) return rc;
+    if (K < 1) return C2R_ERR_INVALID_ARG;
+    if (!x || !ws_gate || !ws_up || !h_shared) return C2R_ERR_INVALID_ARG;
+    if (A_cap > 0 && (!perm || !offsets || !w_gate || !w_up || !h)) return C2R_ERR_INVALID_ARG;
+    if (!aligned(x, 16) || !aligned(w_gate, 16) || !aligned(w_up, 16) || !aligned(h, 16) || !aligned(ws_gate, 16) ||
+        !aligned(ws_up, 16) || !aligned(h_shared, 16))
+        return C2R_ERR_INVALID_ARG;
+    const uint16_t *xs = static_cast<const uint16_t *>(x);
+    const FfnProblem shared = ffn_bf16_dma_problem(0, xs, d, nullptr, 1, T, d, F_shared,
+                                                   static_cast<const uint16_t *>(ws_gate),
+                                                   static_cast<const uint16_t *>(ws_up),
+                                                   static_cast<uint16_t *>(h_shared), F_shared, nullptr, 1, 1);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (A_cap == 0) return launch_ffn_bf16_dma(0, shared, nullptr, st);
+    const FfnProblem routed = ffn_bf16_dma_problem(0, xs, d, offsets, E_local, A_cap, d, F,
+                                                   static_cast<const uint16_t *>(w_gate),
+                                                   static_cast<const uint16_t *>(w_up), static_cast<uint16_t *>(h), F,
+                                                   perm, K, (int)T);
+    return launch_ffn_bf16_dma(0, routed, &shared, st);
+}
+
+extern "C" int c2r_expert_ffn_down_with_shared(const void *h, c2r_dtype dt, const int32_t *offsets, int E_local,
+                                               int64_t A_cap, int d, int F, const void *w_down, void *y_perm,
+                                               int64_t T, int F_shared, const void *h_shared, const void *ws_down,
+                                               void *y_shared, void *stream) {
+    const int rc = check_with_shared(dt, T, E_local, A_cap, d, F, F_shared);
+    if (rc != C2R_OK) return rc;
+    if (!h_shared || !ws_down || !y_shared) return C2R_ERR_INVALID_ARG;
+    if (A_cap > 0 && (!h || !offsets || !w_down || !y_perm)) return C2R_ERR_INVALID_ARG;
+    if (!aligned(h, 16) || !aligned(w_down, 16) || !aligned(y_perm, 16) || !aligned(h_shared, 16) ||
+        !aligned(ws_down, 16) || !aligned(y_shared, 16))
+        return C2R_ERR_INVALID_ARG;
+    const FfnProblem shared = ffn_bf16_dma_problem(1, static_cast<const uint16_t *>(h_shared), F_shared, nullptr, 1, T, d,
+                                                   F_shared, static_cast<const uint16_t *>(ws_down), nullptr,
+                                                   static_cast<uint16_t *>(y_shared), d, nullptr, 1, 1);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (A_cap == 0) return launch_ffn_bf16_dma(1, shared, nullptr, st);
+    const FfnProblem routed = ffn_bf16_dma_problem(1, static_cast<const uint16_t *>(h), F, offsets, E_local, A_cap, d, F,
+                                                   static_cast<const uint16_t *>(w_down), nullptr,
+                                                   static_cast<uint16_t *>(y_perm), d, nullptr, 1, 1);
+    return launch_ffn_bf16_dma(1, routed, &shared, st);
 }

@@ -91,11 +91,7 @@ __device__ __forceinline__ void lds_barrier() {
 }
 
 template <int MODE, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
-    const uint16_t *__restrict__ A, int lda, const int32_t *__restrict__ offsets, int E_local,
-    int A_cap, int N, int Kdim, const uint16_t *__restrict__ B0, const uint16_t *__restrict__ B1,
-    uint16_t *__restrict__ out, int ldo, int ntn, int zero_to, const int32_t *__restrict__ gather,
-    int gather_div, int gather_rows) {
+__global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaunch L) {
     constexpr int BM = 256, BN = 256, BK = 64;
     constexpr int NW = WM * WN;                // waves
     constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
@@ -133,31 +129,80 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
-    // Tile of this workgroup.  One group (a shared expert, a plain GEMM) needs no map: its
-    // bounds are two scalar loads and its tiles all cost the same.
+    // Tile of this workgroup.  The launch carries one problem, or two (the routed groups and an
+    // always-on shared expert).  An XCD's list: its share of the single group's tiles, then of
+    // the ragged problem's full tiles, then of its short tiles (ffn_common.h).  One group (a
+    // shared expert, a plain GEMM) needs no map: its bounds are two scalars.
+    const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
+    auto group_bounds = [&](const FfnProblem &P, int &lo, int &hi) {
+        lo = P.offsets ? P.offsets[0] : P.row_lo;
+        hi = P.offsets ? P.offsets[1] : P.row_hi;
+        lo = lo < 0 ? 0 : (lo > P.A_cap ? P.A_cap : lo);
+        hi = hi < lo ? lo : (hi > P.A_cap ? P.A_cap : hi);
+    };
+    // (the launcher puts the ragged problem, if any, in p[0] and the single group in p[1])
+    const bool ragged0 = L.has_ragged != 0, have_sg = L.has_single != 0;
+    int slo = 0, shi = 0, smt = 0;
+    XcdRange rs, ra, rb;
+    rs.first = rs.cnt = ra.first = ra.cnt = rb.first = rb.cnt = 0;
+    if (have_sg) {
+        group_bounds(L.p[1], slo, shi);
+        smt = (shi - slo + BM - 1) / BM;
+        rs = equal_range(smt * L.p[1].ntn, xcd);
+    }
+    RaggedMap rmap;
+    if (ragged0) {
+        rmap = build_ragged_map<BM>(L.p[0].offsets, L.p[0].E_local, L.p[0].A_cap);
+        ra = equal_range(rmap.totalA * L.p[0].ntn, xcd);
+        rb = equal_range(rmap.totalB * L.p[0].ntn, xcd);
+    }
+    TailSplit ts = split_last_round(rs.cnt + ra.cnt + rb.cnt, slot);
+    if (!ts.valid) return;
+    // (the same in every lane, but derived from cross-lane moves: say so, so that everything
+    // picked by them - the problem's arguments above all - stays in scalar registers)
+    ts.idx = __builtin_amdgcn_readfirstlane(ts.idx);
+    ts.sub = __builtin_amdgcn_readfirstlane(ts.sub);
+    ts.nsub = __builtin_amdgcn_readfirstlane(ts.nsub);
+    const int n_s = __builtin_amdgcn_readfirstlane(rs.cnt), n_a = __builtin_amdgcn_readfirstlane(ra.cnt);
+    // Position in the XCD's list -> item.  The short tiles are SPREAD evenly through the list
+    // (a short tile streams its expert's weights from HBM at what one CU can pull, ~44 GB/s,
+    // with the matrix pipe nearly idle: side by side with compute-bound tiles on the other CUs
+    // that costs nothing but the CU; all of them together at the end or at the start of the
+    // launch is a phase in which the whole chip waits for HBM - measured 36 us per short tile
+    // instead of 28).  The other items keep their order: single group first, then full tiles.
+    const int n_b = __builtin_amdgcn_readfirstlane(rb.cnt), n_all = n_s + n_a + n_b;
+    const int b_before = (int)((uint32_t)ts.idx * (uint32_t)n_b / (uint32_t)n_all);
+    const bool is_b = (int)(((uint32_t)ts.idx + 1u) * (uint32_t)n_b / (uint32_t)n_all) > b_before;
+    const int o_rank = ts.idx - b_before;  // rank among the other items
+    const bool second = !is_b && o_rank < n_s;  // workgroup-uniform: this tile is the single group's (p[1])
     GroupTile g;
-    int tile_nt, tile_nsub;
-    if (E_local == 1) {
-        int lo = offsets[0], hi = offsets[1];
-        lo = lo < 0 ? 0 : (lo > A_cap ? A_cap : lo);
-        hi = hi < lo ? lo : (hi > A_cap ? A_cap : hi);
-        const TileId t1 = xcd_grouped_tile<true>((hi - lo + BM - 1) / BM, ntn);
-        if (!t1.valid) return;
+    int tile_nt;
+    const int tile_nsub = ts.nsub;
+    if (second) {
+        int mt;
+        single_group_tile_at(smt, L.p[1].ntn, rs.first + o_rank, mt, tile_nt);
         g.expert = 0;
-        g.row_begin = lo + t1.mt * BM + t1.sub * (BM / t1.nsub);  // of this workgroup's part of the tile
-        g.row_end = hi;
-        tile_nt = t1.nt;
-        tile_nsub = t1.nsub;
+        g.row_begin = slo + mt * BM + ts.sub * (BM / ts.nsub);  // of this workgroup's part of the tile
+        g.row_end = shi;
     } else {
-        const RaggedMap rmap = build_ragged_map<BM>(offsets, E_local, A_cap);
-        const RaggedTile tr = ragged_tile<BM>(rmap, ntn, (int)(blockIdx.x & 7), (int)(blockIdx.x >> 3));
+        const RaggedTile tr = is_b ? ragged_short_tile_at<BM>(rmap, L.p[0].ntn, rb.first + b_before)
+                                   : ragged_full_tile_at<BM>(rmap, L.p[0].ntn, ra.first + o_rank - n_s);
         if (!tr.valid) return;
         g.expert = tr.expert;
-        g.row_begin = tr.row_begin;
+        g.row_begin = tr.row_begin + ts.sub * (BM / ts.nsub);
         g.row_end = tr.row_end;
         tile_nt = tr.nt;
-        tile_nsub = tr.nsub;
     }
+    // the problem's arguments, uniform over the workgroup from here on
+#define C2R_PICK(f) (second ? L.p[1].f : L.p[0].f)
+    const uint16_t *__restrict__ A = C2R_PICK(A);
+    const uint16_t *__restrict__ B0 = C2R_PICK(B0);
+    const uint16_t *__restrict__ B1 = C2R_PICK(B1);
+    uint16_t *__restrict__ out = C2R_PICK(out);
+    const int32_t *__restrict__ gather = C2R_PICK(gather);
+    const int lda = C2R_PICK(lda), N = C2R_PICK(N), Kdim = C2R_PICK(Kdim), ldo = C2R_PICK(ldo);
+    const int zero_to = C2R_PICK(zero_to), gather_div = C2R_PICK(gather_div), gather_rows = C2R_PICK(gather_rows);
+#undef C2R_PICK
     const int n0 = tile_nt * BNF;
     int rows = g.row_end - g.row_begin;  // may exceed the tile (clamped by the row guards below)
     if (rows <= 0) return;
@@ -604,29 +649,72 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(
     }
 }
 
-// pass 0: a = x_perm [A_cap, d] (d % 64 == 0), out = h with row pitch ldh >= F, columns
-//         [F, ldh) zeroed;   pass 1: a = h (pitch ldh, zero padded to 64), out = y_perm.
+// One problem of a pass.  pass 0: a = x_perm [A_cap, d] (d % 64 == 0) or, with gather, x [T, d];
+// out = h with row pitch ldo >= F, columns [F, ldo) zeroed.  pass 1: a = h (pitch lda, zero
+// padded to 64), out = y_perm.  offsets == nullptr: one group, rows [0, A_cap).
+FfnProblem ffn_bf16_dma_problem(int pass, const uint16_t *a, int lda, const int32_t *offsets, int E_local,
+                                int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1, uint16_t *out,
+                                int ldo, const int32_t *gather, int gather_div, int gather_rows) {
+    constexpr int BN = 256;
+    FfnProblem P;
+    P.A = a;
+    P.offsets = offsets;
+    P.B0 = b0;
+    P.B1 = pass == 0 ? b1 : nullptr;
+    P.out = out;
+    P.gather = pass == 0 ? gather : nullptr;
+    P.lda = lda;
+    P.E_local = E_local;
+    P.A_cap = (int)A_cap;
+    P.N = pass == 0 ? F : d;
+    P.Kdim = pass == 0 ? d : F;
+    P.ldo = ldo;
+    P.ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
+    P.zero_to = pass == 0 ? ldo : 0;
+    P.gather_div = pass == 0 ? gather_div : 1;
+    P.gather_rows = pass == 0 ? gather_rows : 1;
+    P.row_lo = 0;
+    P.row_hi = (int)A_cap;
+    return P;
+}
+
+// Launches one pass over one problem (second == nullptr) or over two in ONE grid: the second
+// must be a single group (E_local == 1).
+int launch_ffn_bf16_dma(int pass, const FfnProblem &first, const FfnProblem *second, hipStream_t st) {
+    drop_stale_error();
+    constexpr int BM = 256, WM = 2, WN = 4;
+    if (second && second->E_local != 1) return C2R_ERR_INVALID_ARG;
+    // the kernel expects the ragged problem (more than one group) in p[0], a single group in p[1]
+    FfnLaunch L;
+    const FfnProblem *single = second ? second : (first.E_local == 1 ? &first : nullptr);
+    const FfnProblem *ragged = first.E_local != 1 ? &first : nullptr;
+    if (second && !ragged) return C2R_ERR_INVALID_ARG;  // (two single groups: launch them one by one)
+    L.p[0] = ragged ? *ragged : *single;
+    L.p[1] = single ? *single : *ragged;
+    L.has_ragged = ragged ? 1 : 0;
+    L.has_single = single ? 1 : 0;
+    int64_t per_xcd = CUS_PER_XCD;
+    if (ragged)
+        per_xcd += ragged_per_xcd_bound(((int64_t)ragged->A_cap + BM - 1) / BM + ragged->E_local, ragged->E_local,
+                                        ragged->ntn);
+    if (single) per_xcd += single_per_xcd_bound(((int64_t)single->A_cap + BM - 1) / BM + 1, single->ntn);
+    const int64_t grid = per_xcd * 8;
+    if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
+    const dim3 g((unsigned)grid), b(WM * WN * 64);
+    if (pass == 0)
+        ffn_bf16_dma_kernel<0, WM, WN><<<g, b, 0, st>>>(L);
+    else
+        ffn_bf16_dma_kernel<1, WM, WN><<<g, b, 0, st>>>(L);
+    return launch_status();
+}
+
 int launch_ffn_bf16_dma_pass(int pass, const uint16_t *a, int lda, const int32_t *offsets, int E_local,
                              int64_t A_cap, int d, int F, const uint16_t *b0, const uint16_t *b1,
                              uint16_t *out, int ldo, const int32_t *gather, int gather_div, int gather_rows,
                              hipStream_t st) {
-    drop_stale_error();
-    constexpr int BM = 256, BN = 256, WM = 2, WN = 4;
-    const int64_t mtiles = (A_cap + BM - 1) / BM + E_local;
-    const int ntn = pass == 0 ? (ldo + BN / 2 - 1) / (BN / 2) : (d + BN - 1) / BN;
-    const int64_t grid = E_local == 1 ? xcd_grouped_grid(mtiles, ntn, true) : ragged_grid(mtiles, ntn);
-    if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
-    const dim3 g((unsigned)grid), b(WM * WN * 64);
-    const uint16_t *no_b1 = nullptr;
-    const int32_t *no_gather = nullptr;
-    if (pass == 0) {
-        ffn_bf16_dma_kernel<0, WM, WN><<<g, b, 0, st>>>(a, lda, offsets, E_local, (int)A_cap, F, d, b0, b1, out, ldo,
-                                                        ntn, ldo, gather, gather_div, gather_rows);
-    } else {
-        ffn_bf16_dma_kernel<1, WM, WN><<<g, b, 0, st>>>(a, lda, offsets, E_local, (int)A_cap, d, F, b0, no_b1, out, ldo,
-                                                        ntn, 0, no_gather, 1, 1);
-    }
-    return launch_status();
+    const FfnProblem P = ffn_bf16_dma_problem(pass, a, lda, offsets, E_local, A_cap, d, F, b0, b1, out, ldo, gather,
+                                              gather_div, gather_rows);
+    return launch_ffn_bf16_dma(pass, P, nullptr, st);
 }
 
 }  // namespace c2r

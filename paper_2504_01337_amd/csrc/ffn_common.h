@@ -153,27 +153,27 @@ static inline int64_t xcd_grouped_grid(int64_t mtiles_bound, int ntn, bool split
 }
 
 // ---- Ragged tile map of the fast bf16 kernel --------------------------------------------
-// Tiles are numbered expert after expert; inside an expert in chunks of TILE_GM M-tiles, and
-// inside a chunk N-tile after N-tile with the chunk's M-tiles fastest.  A chunk never spans
-// two experts, so the ~32 workgroups that run together on an XCD stream each expert's
-// weight k-slices once per chunk (with chunks of consecutive M-tiles regardless of expert,
-// a chunk held 2-3 small experts and streamed all of their weights: measured 2.2 x the
-// weight bytes at the Qwen-MoE shape).  Each XCD gets a contiguous range of tile numbers of
-// equal estimated COST, not equal count: an M-tile of at most BM/2 rows (only an expert's
-// last one can be) runs the short path, which is bound by streaming the expert's weights and
-// counted as two thirds of a full tile (weights 3 : 2 measured 0.5-1 % faster per pass than
-// 2 : 1, 3 : 1 and 1 : 1), and ranges of equal count were measured 6 % apart in cost on
-// Zipf-sized experts.  A boundary moves at
-// most 1/64 of the tiles away from its equal-count position, which bounds the workgroups a
-// launch needs (ragged_grid) without knowing the group sizes on the host.
-// estimated cost of an M-tile: full, and an expert's last one if it has at most BM/2 rows
-#define C2R_COST_FULL 3
-#define C2R_COST_SHORT 2
+// M-tiles of BM rows are cut expert after expert; they fall into two classes.  FULL tiles hold
+// more than BM/2 rows and are bound by the matrix pipe; a SHORT tile (at most BM/2 rows: only
+// an expert's last one can be) is bound by streaming its expert's weights and takes about two
+// thirds of a full tile's time however few rows it holds.  The classes are numbered apart:
+//   class A  full tiles, expert after expert; inside an expert in chunks of TILE_GM M-tiles,
+//            inside a chunk N-tile after N-tile with the chunk's M-tiles fastest, so that the
+//            ~32 workgroups that run together on an XCD form a block of ONE expert's tiles
+//            and share its k-slices in that XCD's L2 (a chunk never spans two experts);
+//   class B  short tiles, expert after expert, N-tile after N-tile.
+// Every XCD gets an equal COUNT of each class (a contiguous range of its numbers): tiles of a
+// class cost the same, so the XCDs' loads are equal without a cost model, and the short tiles
+// run LAST: an XCD hands its list out to whichever CU is free, so what decides the idle tail
+// at the end of a launch is the length of the last items, and these are the shortest.
+// (Before: one numbering with ranges of equal estimated cost, short tiles where their expert
+// stood.  Measured at the Qwen-MoE shape: the XCDs finished 20-50 us apart and the CUs of an
+// XCD idled 22 us at the end of each routed pass.)
 struct RaggedMap {
-    int lo, hi;        // this lane's expert: row range (clamped to [0, A_cap])
-    int tiles, first;  // its M-tiles and its first M-tile number
-    int cost, pcost;   // C2R_COST_FULL per M-tile, C2R_COST_SHORT for a short last one; exclusive prefix over experts
-    int total_mtiles, total_cost;  // wave-uniform
+    int lo, hi;            // this lane's expert: row range (clamped to [0, A_cap])
+    int full, shortt;      // its full M-tiles; 1 if its last M-tile is a short one
+    int firstA, firstB;    // exclusive prefixes of the two over the experts
+    int totalA, totalB;    // wave-uniform totals
 };
 
 template <int BM>
@@ -182,82 +182,38 @@ __device__ __forceinline__ RaggedMap build_ragged_map(const int32_t *__restrict_
     RaggedMap m;
     m.lo = gm.lo;
     m.hi = gm.hi;
-    m.tiles = gm.tiles;
-    m.first = gm.first;
-    m.total_mtiles = gm.total_mtiles;
     const int cnt = gm.hi - gm.lo;
-    const bool short_last = gm.tiles > 0 && cnt - (gm.tiles - 1) * BM <= BM / 2;
-    m.cost = C2R_COST_FULL * gm.tiles - (short_last ? C2R_COST_FULL - C2R_COST_SHORT : 0);
-    const int incl = wave_inclusive_scan(m.cost);
-    m.pcost = incl - m.cost;
-    m.total_cost = __builtin_amdgcn_readfirstlane(__shfl(incl, 63));
+    m.shortt = (gm.tiles > 0 && cnt - (gm.tiles - 1) * BM <= BM / 2) ? 1 : 0;
+    m.full = gm.tiles - m.shortt;
+    // one scan for both: the short-tile count rides in the high half (at most 64 of them)
+    const int incl = wave_inclusive_scan(m.full | (m.shortt << 24));
+    const int excl = incl - (m.full | (m.shortt << 24));
+    m.firstA = excl & 0xffffff;
+    m.firstB = excl >> 24;
+    const int tot = __builtin_amdgcn_readlane(incl, 63);
+    m.totalA = tot & 0xffffff;
+    m.totalB = tot >> 24;
     return m;
 }
 
-// First tile number of XCD x's range (x = 8: one past the last tile).  Same result in every
-// wave of the launch: integer arithmetic on the same map.
-__device__ __forceinline__ int ragged_boundary(const RaggedMap &m, int ntn, int x) {
-    const int total = m.total_mtiles * ntn;
-    if (x <= 0) return 0;
-    if (x >= 8) return total;
-    const int even = (int)((uint64_t)(uint32_t)total * (uint32_t)x / 8u), win = total / 64;
-    const uint64_t G = (uint64_t)(uint32_t)ntn * (uint32_t)m.total_cost;  // < 2^32 (launcher check)
-    const uint32_t g = (uint32_t)(G * (uint32_t)x / 8u);
-    const uint32_t clo = (uint32_t)ntn * (uint32_t)m.pcost, chi = clo + (uint32_t)ntn * (uint32_t)m.cost;
-    const uint64_t hit = __ballot(m.cost > 0 && g >= clo && g < chi);
-    if (hit == 0) return even;
-    const int e = __ffsll((unsigned long long)hit) - 1;
-    const int tiles = __builtin_amdgcn_readlane(m.tiles, e), first = __builtin_amdgcn_readlane(m.first, e);
-    const int cost = __builtin_amdgcn_readlane(m.cost, e), pc = __builtin_amdgcn_readlane(m.pcost, e);
-    const uint32_t r = g - (uint32_t)ntn * (uint32_t)pc;  // cost offset inside the expert
-    const int sh = C2R_COST_FULL * tiles - cost;           // > 0: the last M-tile is short (full - short cost)
-    const int gl = tiles - TILE_GM * ((tiles - 1) / TILE_GM);  // M-tiles of the last chunk
-    const uint32_t R = (uint32_t)C2R_COST_FULL * (uint32_t)(tiles - gl) * (uint32_t)ntn;  // cost of the full chunks
-    uint32_t t;
-    if (r < R)
-        t = r / (uint32_t)C2R_COST_FULL;
-    else  // the last chunk's tiles cost (2 gl - sh) / gl on average (its M-tiles alternate)
-        t = (uint32_t)(tiles - gl) * (uint32_t)ntn + (r - R) * (uint32_t)gl / (uint32_t)(C2R_COST_FULL * gl - sh);
-    const int b = first * ntn + (int)t;
-    return b < even - win ? even - win : (b > even + win ? even + win : b);
-}
-
 struct RaggedTile {
-    int expert, row_begin, row_end;  // row_begin: first row of the tile (part); row_end: the expert's end
+    int expert, row_begin, row_end;  // row_begin: first row of the tile; row_end: the expert's end
     int nt;
-    int sub, nsub;  // the tile's rows are cut into nsub equal parts and this workgroup owns part sub
     bool valid;
 };
 
-// Workgroup (XCD, slot) -> tile.  The tiles an XCD has left after its last full round of
-// CUS_PER_XCD are cut along M into 2 or 4 row parts, each its own workgroup, so that the
-// last round occupies the CUs that would idle; the parts are dispatched last.
+// Class A tile number -> tile.
 template <int BM>
-__device__ __forceinline__ RaggedTile ragged_tile(const RaggedMap &m, int ntn, int xcd, int slot) {
+__device__ __forceinline__ RaggedTile ragged_full_tile_at(const RaggedMap &m, int ntn, int tile) {
     RaggedTile t;
     t.valid = false;
     t.expert = -1;
-    t.row_begin = t.row_end = t.nt = t.sub = 0;
-    t.nsub = 1;
-    const int b0 = ragged_boundary(m, ntn, xcd), b1 = ragged_boundary(m, ntn, xcd + 1);
-    const int cnt = b1 - b0;
-    if (cnt <= 0) return t;
-    int idx = slot;
-    const int full = cnt / CUS_PER_XCD * CUS_PER_XCD, r = cnt - full;
-    const int s = r == 0 ? 1 : (r * 4 <= CUS_PER_XCD ? 4 : (r * 2 <= CUS_PER_XCD ? 2 : 1));
-    if (slot >= full) {
-        const int q = slot - full;
-        if (q >= r * s) return t;
-        idx = full + q / s;
-        t.sub = q % s;
-        t.nsub = s;
-    }
-    const int tile = b0 + idx;
-    const int tlo = m.first * ntn;
-    const uint64_t hit = __ballot(m.tiles > 0 && tile >= tlo && tile < tlo + m.tiles * ntn);
+    t.row_begin = t.row_end = t.nt = 0;
+    const int tlo = m.firstA * ntn;
+    const uint64_t hit = __ballot(m.full > 0 && tile >= tlo && tile < tlo + m.full * ntn);
     if (hit == 0) return t;
     const int e = __ffsll((unsigned long long)hit) - 1;
-    const int tiles = __builtin_amdgcn_readlane(m.tiles, e), first = __builtin_amdgcn_readlane(m.first, e);
+    const int tiles = __builtin_amdgcn_readlane(m.full, e), first = __builtin_amdgcn_readlane(m.firstA, e);
     const int tp = tile - first * ntn;
     const int c = tp / (TILE_GM * ntn);
     const int gsz = tiles - c * TILE_GM < TILE_GM ? tiles - c * TILE_GM : TILE_GM;
@@ -265,18 +221,109 @@ __device__ __forceinline__ RaggedTile ragged_tile(const RaggedMap &m, int ntn, i
     const int mloc = c * TILE_GM + rem % gsz;
     t.nt = rem / gsz;
     t.expert = e;
-    t.row_begin = __builtin_amdgcn_readlane(m.lo, e) + mloc * BM + t.sub * (BM / t.nsub);
+    t.row_begin = __builtin_amdgcn_readlane(m.lo, e) + mloc * BM;
     t.row_end = __builtin_amdgcn_readlane(m.hi, e);
     t.valid = true;
     return t;
 }
 
-// Host side: workgroups to launch for the ragged map: a range holds at most 1/8 + 2/64 of
-// the tiles (+1 for rounding), plus the split last round.
-static inline int64_t ragged_grid(int64_t mtiles_bound, int ntn) {
-    const int64_t total = mtiles_bound * ntn;
-    const int64_t per_xcd = (total + 7) / 8 + 2 * (total / 64) + 2;
-    return (per_xcd + CUS_PER_XCD) * 8;
+// Class B tile number -> tile.
+template <int BM>
+__device__ __forceinline__ RaggedTile ragged_short_tile_at(const RaggedMap &m, int ntn, int tile) {
+    RaggedTile t;
+    t.valid = false;
+    t.expert = -1;
+    t.row_begin = t.row_end = t.nt = 0;
+    const int tlo = m.firstB * ntn;
+    const uint64_t hit = __ballot(m.shortt > 0 && tile >= tlo && tile < tlo + ntn);
+    if (hit == 0) return t;
+    const int e = __ffsll((unsigned long long)hit) - 1;
+    t.nt = tile - __builtin_amdgcn_readlane(m.firstB, e) * ntn;
+    t.expert = e;
+    t.row_begin = __builtin_amdgcn_readlane(m.lo, e) + __builtin_amdgcn_readlane(m.full, e) * BM;
+    t.row_end = __builtin_amdgcn_readlane(m.hi, e);
+    t.valid = true;
+    return t;
 }
+
+// ---- An XCD's list.  A launch carries one problem or TWO (the routed groups and an always-on
+// shared expert, a single group).  The list of an XCD is: its share of the single group's
+// tiles (the longest items first: at the Qwen-MoE shape a tile of the shared expert's down
+// pass runs 88 k-slices, a routed one 22), then its share of the ragged problem's full tiles,
+// then its share of the short tiles; the last round of the COMBINED list is cut into row
+// parts. ----
+struct XcdRange {
+    int first, cnt;  // first tile number and number of tiles of one XCD
+};
+
+__device__ __forceinline__ void single_group_tile_at(int total_mtiles, int ntn, int tile, int &mt, int &nt) {
+    const int grp = tile / (TILE_GM * ntn);
+    const int first_m = grp * TILE_GM;
+    const int gsz = total_mtiles - first_m < TILE_GM ? total_mtiles - first_m : TILE_GM;
+    const int rem = tile - grp * TILE_GM * ntn;
+    mt = first_m + rem % gsz;
+    nt = rem / gsz;
+}
+
+// An equal share of n numbered tiles for each of the 8 XCDs (contiguous ranges).
+__device__ __forceinline__ XcdRange equal_range(int n, int xcd) {
+    XcdRange r;
+    const int per_xcd = (n + 7) / 8;
+    r.first = xcd * per_xcd;
+    int cnt = n - r.first;
+    cnt = cnt > per_xcd ? per_xcd : cnt;
+    r.cnt = cnt > 0 ? cnt : 0;
+    return r;
+}
+
+// Slot of an XCD's list of cnt tiles -> tile index in the list and row part.  The tiles left
+// after the last full round of CUS_PER_XCD are cut along M into 2 or 4 parts, each a workgroup
+// of its own (at most CUS_PER_XCD of them), so that the last round occupies the CUs that
+// would idle; the parts are dispatched last.
+struct TailSplit {
+    int idx, sub, nsub;
+    bool valid;
+};
+
+__device__ __forceinline__ TailSplit split_last_round(int cnt, int slot) {
+    TailSplit t;
+    t.idx = slot;
+    t.sub = 0;
+    t.nsub = 1;
+    t.valid = false;
+    if (cnt <= 0) return t;
+    const int full = cnt / CUS_PER_XCD * CUS_PER_XCD, r = cnt - full;
+    const int s = r == 0 ? 1 : (r * 4 <= CUS_PER_XCD ? 4 : (r * 2 <= CUS_PER_XCD ? 2 : 1));
+    if (slot >= full) {
+        const int q = slot - full;
+        if (q >= r * s) return t;
+        t.idx = full + q / s;
+        t.sub = q % s;
+        t.nsub = s;
+    }
+    t.valid = true;
+    return t;
+}
+
+// Host side: bound on the tiles one XCD may get from a ragged problem (its share of the full
+// tiles plus its share of at most one short tile per expert) / from a single group.
+static inline int64_t ragged_per_xcd_bound(int64_t mtiles_bound, int E_local, int ntn) {
+    return (mtiles_bound * ntn + 7) / 8 + ((int64_t)E_local * ntn + 7) / 8;
+}
+static inline int64_t single_per_xcd_bound(int64_t mtiles_bound, int ntn) { return (mtiles_bound * ntn + 7) / 8; }
+
+// One problem of a fast bf16 FFN launch (see ffn_bf16_dma.hip); a launch carries one or two.
+struct FfnProblem {
+    const uint16_t *A;        // activations [rows, lda] (or, with gather, the un-permuted [T, lda])
+    const int32_t *offsets;   // DEVICE int32[E_local + 1]; nullptr: one group, rows [row_lo, row_hi)
+    const uint16_t *B0, *B1;  // weights [E_local, N, Kdim] (B1: the up projection of pass 0)
+    uint16_t *out;            // [rows, ldo]
+    const int32_t *gather;    // row p of the sorted order is A[gather[p] / gather_div], or nullptr
+    int lda, E_local, A_cap, N, Kdim, ldo, ntn, zero_to, gather_div, gather_rows, row_lo, row_hi;
+};
+struct FfnLaunch {
+    FfnProblem p[2];            // p[0]: the ragged problem (several groups), p[1]: the single group
+    int has_ragged, has_single;  // which of the two the launch carries (at least one)
+};
 
 }  // namespace c2r

@@ -84,6 +84,11 @@ def test_argument_errors_before_launch():
     assert L.c2r_distinct_devices(p, 16, 2, 8, p, 2, 4, null, null, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_distinct_devices(p, 16, 2, 8, p, 2, 4, null, ctypes.c_void_p(0x1004), null) == c2r.ERR_INVALID_ARG
     assert c2r.workspace_bytes(c2r.STAGE_DEDUP_DISPATCH, 5000, 0, 4, 4, 0, c2r.F32) == 256
+    assert L.c2r_expert_ffn_gate_up_with_shared(p, 0, p, 16, 2, p, 4, 32, 64, 64, p, p, p, 64, p, p, p, null) == c2r.ERR_UNSUPPORTED  # fp32
+    assert L.c2r_expert_ffn_gate_up_with_shared(p, 1, p, 16, 2, p, 4, 32, 64, 64, p, p, p, 72, p, p, p, null) == c2r.ERR_UNSUPPORTED  # F_shared % 64
+    assert L.c2r_expert_ffn_gate_up_with_shared(p, 1, p, 16, 2, p, 4, 32, 64, 64, p, p, p, 64, null, p, p, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_expert_ffn_down_with_shared(p, 1, p, 4, 32, 64, 64, p, p, 16, 64, p, p, null, null) == c2r.ERR_INVALID_ARG
+    assert L.c2r_expert_ffn_down_with_shared(p, 1, p, 4, 32, 64, 88, p, p, 16, 64, p, p, p, null) == c2r.ERR_UNSUPPORTED  # F % 64
     # the allocation-free dispatch rejects what its static array cannot hold
     assert L.c2r_permute_noalloc(p, 1, p, (1 << 20) + 1, 64, 8, 4, null, 8, p, p, p, p, p, null) == c2r.ERR_UNSUPPORTED
     # empty batches are fine and launch nothing

@@ -312,6 +312,46 @@ def test_ffn_gather_equals_ffn_on_x_perm(c2r, E, K, T, d, F, local):
     assert n > 0 and torch.all(y1[n:] == 7.0) and not torch.all(y1[:n] == 7.0)
 
 
+@pytest.mark.parametrize("E,K,T,d,F,Fs,local", [(60, 4, 700, 128, 192, 448, False), (7, 2, 300, 64, 64, 64, False),
+                                                   (16, 4, 1500, 256, 128, 640, True), (5, 1, 64, 64, 128, 192, False)])
+def test_ffn_with_shared_equals_separate_launches(c2r, E, K, T, d, F, Fs, local):
+    # routed groups + always-on shared expert in one launch per pass: the same bits as the
+    # separate launches (gather-fused routed passes; shared expert with E_local = 1 on x)
+    rng = np.random.default_rng(E * 1000 + T)
+    idx = rng.integers(0, E, size=(T, K)).astype(np.int32)
+    idx[::9, 0] = -1
+    if local:
+        ls = np.full(E, -1, dtype=np.int32)
+        keep = np.sort(rng.permutation(E)[: E // 2])
+        ls[keep] = np.arange(len(keep), dtype=np.int32)
+        El = len(keep)
+    else:
+        ls, El = None, E
+    x = dev(rng.standard_normal((T, d)).astype(np.float32), "bf16")
+    w = lambda *sh: dev((rng.standard_normal(sh) * 0.05).astype(np.float32), "bf16")
+    wg, wu, wd = w(El, F, d), w(El, F, d), w(El, d, F)
+    sg, su, sd = w(1, Fs, d), w(1, Fs, d), w(1, d, Fs)
+    counts, offsets, perm, inv, _ = c2r.permute(x, dev(idx), E, dev(ls), El, rows=False)
+    A = T * K
+    bf = dict(dtype=torch.bfloat16, device="cuda")
+    h1, hs1 = torch.zeros(A, F, **bf), torch.zeros(T, Fs, **bf)
+    y1, ys1 = torch.zeros(A, d, **bf), torch.zeros(T, d, **bf)
+    h2, hs2, y2, ys2 = (torch.zeros_like(t) for t in (h1, hs1, y1, ys1))
+    off_s = torch.tensor([0, T], dtype=torch.int32, device="cuda")
+    c2r.expert_ffn_gate_up_gather(x, perm, K, offsets, wg, wu, h1)
+    c2r.expert_ffn_gate_up(x, off_s, sg, su, hs1)
+    c2r.expert_ffn_down(h1, offsets, wd, y1)
+    c2r.expert_ffn_down(hs1, off_s, sd, ys1)
+    c2r.expert_ffn_gate_up_with_shared(x, perm, K, offsets, wg, wu, h2, sg, su, hs2)
+    c2r.expert_ffn_down_with_shared(h2, offsets, wd, y2, hs2, sd, ys2)
+    torch.cuda.synchronize()
+    n = int(offsets[-1])
+    assert n > 0
+    assert torch.equal(h1[:n], h2[:n]) and torch.equal(hs1, hs2)
+    assert torch.equal(y1[:n], y2[:n]) and torch.equal(ys1, ys2)
+    assert not y2[n:].any() and not h2[n:].any()          # rows past the groups are untouched
+
+
 def test_gate_up_gather_rejects_other_shapes(c2r):
     x = torch.zeros((8, 72), dtype=torch.float32, device="cuda")
     perm = torch.zeros((8,), dtype=torch.int32, device="cuda")
