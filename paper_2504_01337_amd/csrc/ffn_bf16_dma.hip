@@ -20,6 +20,7 @@
 // Contract (checked by the launcher): the contraction length seen by A is padded to a
 // multiple of 64 with zeros (lda >= 64 * ceil(K/64)); a B chunk past K is re-read from
 // chunk 0 of the same row and multiplied by those zeros.
+#include <atomic>
 #include <type_traits>
 
 #include "ffn_common.h"
@@ -90,8 +91,40 @@ __device__ __forceinline__ void lds_barrier() {
 #endif
 }
 
-template <int MODE, int WM, int WN>
-__global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaunch L) {
+// The launch arguments as the tile function reads them: through the constant address space
+// (scalar loads from the kernel-argument segment).
+typedef const __attribute__((address_space(4))) FfnLaunch FfnLaunchConst;
+typedef const __attribute__((address_space(4))) FfnProblem FfnProblemConst;
+typedef FfnLaunchConst *FfnLaunchArgs;
+
+// Shapes shared by the per-tile function and the kernel around it.
+template <int WM, int WN>
+struct FfnShape {
+    static constexpr int BM = 256, BN = 256, BK = 64, NW = WM * WN, ROWB = BK * 2;
+    static constexpr int A_BYTES = BM * ROWB, B_BYTES = BN * ROWB;
+    static constexpr int LONG_BYTES = 2 * A_BYTES + 3 * B_BYTES;         // 2 A stages + a ring of 3 B stages
+    static constexpr int SHORT_BYTES = 3 * (128 + BN) * ROWB;            // ring of 3 x (128 A rows + B tile)
+    static constexpr int SMEM_BYTES = LONG_BYTES > SHORT_BYTES ? LONG_BYTES : SHORT_BYTES;
+};
+
+// Length of XCD x's list (tiles, with the last round cut into parts): what its queue hands out.
+__device__ __forceinline__ int xcd_list_slots(int n_tiles) {
+    if (n_tiles <= 0) return 0;
+    const int full = n_tiles / CUS_PER_XCD * CUS_PER_XCD, r = n_tiles - full;
+    const int s = r == 0 ? 1 : (r * 4 <= CUS_PER_XCD ? 4 : (r * 2 <= CUS_PER_XCD ? 2 : 1));
+    return full + r * s;
+}
+
+// One output tile: position `slot` of XCD `xcd`'s list.  Every wave of the workgroup calls it
+// with the same arguments; it returns early (all waves alike) when the position holds nothing.
+// grp_lo, grp_hi: the row range of this lane's expert of the ragged problem (load_group_range).
+// before_epilogue(): called once by every wave after the tile's last k-step (the kernel draws
+// the next ticket there, so that the trip to the counter overlaps the epilogue); not called on
+// the early returns.
+template <int MODE, int WM, int WN, class BeforeEpilogue>
+__device__ __forceinline__ void ffn_tile(const FfnLaunchArgs Lp, unsigned char *smem, const int xcd, const int slot,
+                                         const int grp_lo, const int grp_hi, BeforeEpilogue &&before_epilogue) {
+    const FfnLaunchConst &L = *Lp;
     constexpr int BM = 256, BN = 256, BK = 64;
     constexpr int NW = WM * WN;                // waves
     constexpr int TM = BM / WM, TN = BN / WN;  // wave tile
@@ -117,15 +150,19 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
     static_assert(TM_T / 8 == NW, "one A copy group per wave on the tiny path");
     constexpr int SMEM_BYTES = LONG_BYTES > L_NSTAGE * L_STAGE_BYTES ? LONG_BYTES : L_NSTAGE * L_STAGE_BYTES;
     static_assert(T_NSTAGE * T_STAGE_BYTES <= SMEM_BYTES, "the tiny ring fits");
-    static_assert(SMEM_BYTES <= 160 * 1024, "one workgroup per CU owns all of its LDS");
+    static_assert(SMEM_BYTES == FfnShape<WM, WN>::SMEM_BYTES, "the kernel allocates what the tile function lays out");
     static_assert(LM == TM && (LM / 8) % NW == 0, "the short path is the first wave row's M range");
-    __shared__ __attribute__((aligned(1024))) unsigned char smem[SMEM_BYTES];
     unsigned char *const st0 = smem, *const st1 = smem + A_BYTES;  // the two A stages
     // B ring slot q lives at smem + 2*A_BYTES + q*B_BYTES.  Copies and fragment reads address B
     // as "stage + A_BYTES + ...", so a B slot is handed to them as the pointer A_BYTES below it.
     unsigned char *bcur = smem + A_BYTES, *bnxt = bcur + B_BYTES, *bwr = bnxt + B_BYTES;
 
-    const int tid = threadIdx.x, lane = tid & 63;
+    // (the thread index is made opaque per tile: what is derived from it - copy offsets, fragment
+    // addresses - is then recomputed per tile instead of being hoisted out of the kernel's tile
+    // loop and held in registers across it)
+    int tid_opaque = threadIdx.x;
+    asm volatile("" : "+v"(tid_opaque));
+    const int tid = tid_opaque, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
 
@@ -133,8 +170,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
     // always-on shared expert).  An XCD's list: its share of the single group's tiles, then of
     // the ragged problem's full tiles, then of its short tiles (ffn_common.h).  One group (a
     // shared expert, a plain GEMM) needs no map: its bounds are two scalars.
-    const int xcd = (int)(blockIdx.x & 7), slot = (int)(blockIdx.x >> 3);
-    auto group_bounds = [&](const FfnProblem &P, int &lo, int &hi) {
+    auto group_bounds = [&](const FfnProblemConst &P, int &lo, int &hi) {
         lo = P.offsets ? P.offsets[0] : P.row_lo;
         hi = P.offsets ? P.offsets[1] : P.row_hi;
         lo = lo < 0 ? 0 : (lo > P.A_cap ? P.A_cap : lo);
@@ -152,7 +188,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
     }
     RaggedMap rmap;
     if (ragged0) {
-        rmap = build_ragged_map<BM>(L.p[0].offsets, L.p[0].E_local, L.p[0].A_cap);
+        rmap = ragged_map_of<BM>(grp_lo, grp_hi);
         ra = equal_range(rmap.totalA * L.p[0].ntn, xcd);
         rb = equal_range(rmap.totalB * L.p[0].ntn, xcd);
     }
@@ -170,9 +206,17 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
     // that costs nothing but the CU; all of them together at the end or at the start of the
     // launch is a phase in which the whole chip waits for HBM - measured 36 us per short tile
     // instead of 28).  The other items keep their order: single group first, then full tiles.
-    const int n_b = __builtin_amdgcn_readfirstlane(rb.cnt), n_all = n_s + n_a + n_b;
-    const int b_before = (int)((uint32_t)ts.idx * (uint32_t)n_b / (uint32_t)n_all);
-    const bool is_b = (int)(((uint32_t)ts.idx + 1u) * (uint32_t)n_b / (uint32_t)n_all) > b_before;
+    // ... except that the LAST few short tiles of the range close the list: the CUs that run out
+    // of full tiles first take them while the others finish their last full tile, which fills
+    // part of the idle tail of the launch with work that would otherwise sit in the middle of
+    // it (few enough of them that they do not have to share HBM: FILL_TAIL per XCD).
+    constexpr int FILL_TAIL = 12;
+    const int n_b = __builtin_amdgcn_readfirstlane(rb.cnt);
+    const int n_tail = n_b < FILL_TAIL ? n_b : FILL_TAIL, n_bi = n_b - n_tail, n_main = n_s + n_a + n_bi;
+    const bool in_tail = ts.idx >= n_main;
+    const int b_before = in_tail ? n_bi + (ts.idx - n_main)
+                                 : (int)((uint32_t)ts.idx * (uint32_t)n_bi / (uint32_t)(n_main > 0 ? n_main : 1));
+    const bool is_b = in_tail || (int)(((uint32_t)ts.idx + 1u) * (uint32_t)n_bi / (uint32_t)(n_main > 0 ? n_main : 1)) > b_before;
     const int o_rank = ts.idx - b_before;  // rank among the other items
     const bool second = !is_b && o_rank < n_s;  // workgroup-uniform: this tile is the single group's (p[1])
     GroupTile g;
@@ -194,15 +238,14 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
         tile_nt = tr.nt;
     }
     // the problem's arguments, uniform over the workgroup from here on
-#define C2R_PICK(f) (second ? L.p[1].f : L.p[0].f)
-    const uint16_t *__restrict__ A = C2R_PICK(A);
-    const uint16_t *__restrict__ B0 = C2R_PICK(B0);
-    const uint16_t *__restrict__ B1 = C2R_PICK(B1);
-    uint16_t *__restrict__ out = C2R_PICK(out);
-    const int32_t *__restrict__ gather = C2R_PICK(gather);
-    const int lda = C2R_PICK(lda), N = C2R_PICK(N), Kdim = C2R_PICK(Kdim), ldo = C2R_PICK(ldo);
-    const int zero_to = C2R_PICK(zero_to), gather_div = C2R_PICK(gather_div), gather_rows = C2R_PICK(gather_rows);
-#undef C2R_PICK
+    const FfnProblemConst &P = L.p[second ? 1 : 0];  // (a scalar address: the fields are scalar loads)
+    const uint16_t *__restrict__ A = P.A;
+    const uint16_t *__restrict__ B0 = P.B0;
+    const uint16_t *__restrict__ B1 = P.B1;
+    uint16_t *__restrict__ out = P.out;
+    const int32_t *__restrict__ gather = P.gather;
+    const int lda = P.lda, N = P.N, Kdim = P.Kdim, ldo = P.ldo;
+    const int zero_to = P.zero_to, gather_div = P.gather_div, gather_rows = P.gather_rows;
     const int n0 = tile_nt * BNF;
     int rows = g.row_end - g.row_begin;  // may exceed the tile (clamped by the row guards below)
     if (rows <= 0) return;
@@ -578,6 +621,7 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
 #undef C2R_MFMA_ROW
 #undef C2R_MFMA
 
+    before_epilogue();
     // ---- epilogue.  Fragment (i, j) holds C^T: lane (fr, fq), register v is
     //      row m = i*16 + fr, column n = j*16 + 4*fq + v.  Every wave of the workgroup is
     //      here at once with the matrix pipe idle, so the common case (all of the tile's
@@ -649,6 +693,110 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
     }
 }
 
+// Work queues of the launches in flight: per launch one set of 8 ticket counters (one per XCD)
+// and a count of the workgroups that have left.  All zero between launches: the last workgroup
+// to leave a launch clears the set it used.  The host hands the sets out round-robin, so up to
+// FFN_QUEUE_SETS launches of this kernel may be in flight on a GPU at once (on any streams).
+constexpr int FFN_QUEUE_SETS = 64, FFN_QUEUE_INTS = 16;
+__device__ int ffn_queues[FFN_QUEUE_SETS * FFN_QUEUE_INTS];
+
+// The kernel: one workgroup per CU, each pulling tiles until none are left.  The hardware hands
+// workgroups out strictly in order, the k-th of an XCD to shader engine k mod 4 - measured: a CU
+// freed early by a short tile stayed empty for 100 us behind a workgroup that waited for a CU
+// of ANOTHER engine - so with one workgroup per tile every tile shorter than its neighbours
+// left a bubble, and the ragged groups' tiles differ by a factor of six.  Here the list of an
+// XCD (ffn_common.h) is a queue: a ticket counter in device memory that the workgroups of that
+// XCD draw from (the L2 locality of the list is kept), and a workgroup whose own XCD has
+// nothing left draws from the others'.
+template <int MODE, int WM, int WN>
+__global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaunch L, int *__restrict__ queues) {
+    typedef FfnShape<WM, WN> S;
+    static_assert(S::SMEM_BYTES <= 160 * 1024, "one workgroup per CU owns all of its LDS");
+    __shared__ __attribute__((aligned(1024))) unsigned char smem[S::SMEM_BYTES];
+    // The claimed position (XCD of the list, slot; -1: nothing left) is handed to the waves in
+    // the last bytes of the stage memory, which is all of the CU's LDS: every layout of a tile
+    // writes them only after its first hand-over barrier (the third weight stage of a full
+    // tile, the fourth ring stage of a tiny one; a short tile never does), and no wave gets
+    // there before every wave has read the claim.
+    int *const claim = reinterpret_cast<int *>(smem + S::SMEM_BYTES - 64);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int home = (int)(blockIdx.x & 7);
+    // every wave keeps the row range of "its lane's" expert of the ragged problem (the tile
+    // lookup is wave-wide arithmetic on them; they do not change during the launch)
+    int grp_lo = 0, grp_hi = 0;
+    if (L.has_ragged) load_group_range(L.p[0].offsets, L.p[0].E_local, L.p[0].A_cap, grp_lo, grp_hi);
+    // the first wave works the queues; its lane x < 8 keeps the number of slots of XCD x's list
+    int my_len = 0;
+    if (tid < 64) {
+        int n_s = 0;
+        if (L.has_single) {
+            int lo = L.p[1].offsets ? L.p[1].offsets[0] : L.p[1].row_lo;
+            int hi = L.p[1].offsets ? L.p[1].offsets[1] : L.p[1].row_hi;
+            lo = lo < 0 ? 0 : (lo > L.p[1].A_cap ? L.p[1].A_cap : lo);
+            hi = hi < lo ? lo : (hi > L.p[1].A_cap ? L.p[1].A_cap : hi);
+            n_s = (hi - lo + S::BM - 1) / S::BM * L.p[1].ntn;
+        }
+        int totA = 0, totB = 0;
+        if (L.has_ragged) {
+            const RaggedMap m = ragged_map_of<S::BM>(grp_lo, grp_hi);
+            totA = m.totalA * L.p[0].ntn;
+            totB = m.totalB * L.p[0].ntn;
+        }
+        const int x = lane & 7;
+        my_len = xcd_list_slots(equal_range(n_s, x).cnt + equal_range(totA, x).cnt + equal_range(totB, x).cnt);
+    }
+    int q = home;        // the queue this workgroup draws from: its own XCD's until that is empty
+    int ticket = -1;     // (lane 0 of the first wave) a ticket of queue q drawn ahead, -1: none
+    bool drawn = false;  // a ticket has been drawn ahead
+    for (;;) {
+        if (tid < 64) {
+            int t = -1;
+            for (int tries = 0; tries < 8; ++tries) {
+                const int len = __builtin_amdgcn_readlane(my_len, q);
+                if (len > 0) {
+                    if (!drawn && lane == 0) ticket = atomicAdd(&queues[q], 1);
+                    drawn = false;
+                    t = __builtin_amdgcn_readfirstlane(ticket);
+                    if (t < len) break;
+                }
+                drawn = false;
+                t = -1;
+                q = (q + 1) & 7;
+            }
+            if (lane == 0) {
+                claim[0] = q;
+                claim[1] = t;
+            }
+        }
+        __syncthreads();  // the claim is visible
+        q = __builtin_amdgcn_readfirstlane(claim[0]);
+        const int slot = __builtin_amdgcn_readfirstlane(claim[1]);
+        if (slot < 0) break;  // every queue is empty
+        // The launch arguments are re-read per tile through a pointer the compiler cannot see
+        // through: held in registers across the tile they are ~50 scalars too many.
+        // (L is the kernel's first argument: it sits at the start of the kernel-argument segment)
+        FfnLaunchArgs Lp = (FfnLaunchArgs)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(Lp));
+        drawn = false;
+        ffn_tile<MODE, WM, WN>(Lp, smem, q, slot, grp_lo, grp_hi, [&]() {
+            // the next ticket of the same queue, drawn while the epilogue runs
+            if (tid == 0) ticket = atomicAdd(&queues[q], 1);
+            drawn = true;
+        });
+        // this wave's stores have left and its LDS reads have returned (and the ticket is here);
+        // then every wave's: the next claim and the next tile's copies may overwrite the stages
+        wait_copies_and_lds();
+        __syncthreads();
+    }
+    // the last workgroup to leave clears the set for the launch that gets it next
+    if (tid == 0) {
+        __threadfence();
+        if (atomicAdd(&queues[8], 1) == (int)gridDim.x - 1) {
+            for (int i = 0; i < 9; ++i) atomicExch(&queues[i], 0);
+        }
+    }
+}
+
 // One problem of a pass.  pass 0: a = x_perm [A_cap, d] (d % 64 == 0) or, with gather, x [T, d];
 // out = h with row pitch ldo >= F, columns [F, ldo) zeroed.  pass 1: a = h (pitch lda, zero
 // padded to 64), out = y_perm.  offsets == nullptr: one group, rows [0, A_cap).
@@ -693,18 +841,31 @@ int launch_ffn_bf16_dma(int pass, const FfnProblem &first, const FfnProblem *sec
     L.p[1] = single ? *single : *ragged;
     L.has_ragged = ragged ? 1 : 0;
     L.has_single = single ? 1 : 0;
-    int64_t per_xcd = CUS_PER_XCD;
+    // one workgroup per CU (fewer if the bound on the tiles is smaller), whatever the number of tiles
+    int64_t tiles = 0;
     if (ragged)
-        per_xcd += ragged_per_xcd_bound(((int64_t)ragged->A_cap + BM - 1) / BM + ragged->E_local, ragged->E_local,
-                                        ragged->ntn);
-    if (single) per_xcd += single_per_xcd_bound(((int64_t)single->A_cap + BM - 1) / BM + 1, single->ntn);
-    const int64_t grid = per_xcd * 8;
-    if (grid >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
+        tiles += 8 * ragged_per_xcd_bound(((int64_t)ragged->A_cap + BM - 1) / BM + ragged->E_local, ragged->E_local,
+                                          ragged->ntn);
+    if (single) tiles += 8 * single_per_xcd_bound(((int64_t)single->A_cap + BM - 1) / BM + 1, single->ntn);
+    tiles += 8 * CUS_PER_XCD;  // (row parts of the last rounds)
+    const int64_t grid = tiles < 8 * CUS_PER_XCD ? tiles : 8 * CUS_PER_XCD;
+    static std::atomic<unsigned> next_set{0};
+    static std::atomic<int *> queue_base[64];  // per device: the address of that device's copy of ffn_queues
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return C2R_ERR_LAUNCH;
+    int *base = queue_base[dev].load();
+    if (!base) {  // (in host code the array's name is only a handle for this query)
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(ffn_queues)) != hipSuccess || !p) return C2R_ERR_LAUNCH;
+        base = static_cast<int *>(p);
+        queue_base[dev].store(base);
+    }
+    int *queues = base + (next_set.fetch_add(1) % FFN_QUEUE_SETS) * FFN_QUEUE_INTS;
     const dim3 g((unsigned)grid), b(WM * WN * 64);
     if (pass == 0)
-        ffn_bf16_dma_kernel<0, WM, WN><<<g, b, 0, st>>>(L);
+        ffn_bf16_dma_kernel<0, WM, WN><<<g, b, 0, st>>>(L, queues);
     else
-        ffn_bf16_dma_kernel<1, WM, WN><<<g, b, 0, st>>>(L);
+        ffn_bf16_dma_kernel<1, WM, WN><<<g, b, 0, st>>>(L, queues);
     return launch_status();
 }
 

@@ -176,16 +176,18 @@ struct RaggedMap {
     int totalA, totalB;    // wave-uniform totals
 };
 
+// From the expert's row range held by each lane (lo, hi: as build_group_map clamps them; lanes
+// past E_local hold an empty range).  Every wave calls this with all 64 lanes active.
 template <int BM>
-__device__ __forceinline__ RaggedMap build_ragged_map(const int32_t *__restrict__ offsets, int E_local, int A_cap) {
-    const GroupMap gm = build_group_map<BM>(offsets, E_local, A_cap);
+__device__ __forceinline__ RaggedMap ragged_map_of(int lo, int hi) {
     RaggedMap m;
-    m.lo = gm.lo;
-    m.hi = gm.hi;
-    const int cnt = gm.hi - gm.lo;
-    m.shortt = (gm.tiles > 0 && cnt - (gm.tiles - 1) * BM <= BM / 2) ? 1 : 0;
-    m.full = gm.tiles - m.shortt;
-    // one scan for both: the short-tile count rides in the high half (at most 64 of them)
+    m.lo = lo;
+    m.hi = hi;
+    const int cnt = hi - lo;
+    const int tiles = (cnt + BM - 1) / BM;
+    m.shortt = (tiles > 0 && cnt - (tiles - 1) * BM <= BM / 2) ? 1 : 0;
+    m.full = tiles - m.shortt;
+    // one scan for both: the short-tile count rides in the high byte (at most 64 of them)
     const int incl = wave_inclusive_scan(m.full | (m.shortt << 24));
     const int excl = incl - (m.full | (m.shortt << 24));
     m.firstA = excl & 0xffffff;
@@ -194,6 +196,19 @@ __device__ __forceinline__ RaggedMap build_ragged_map(const int32_t *__restrict_
     m.totalA = tot & 0xffffff;
     m.totalB = tot >> 24;
     return m;
+}
+
+// This lane's expert's row range, clamped so that a corrupt array cannot send a load out of bounds.
+__device__ __forceinline__ void load_group_range(const int32_t *__restrict__ offsets, int E_local, int A_cap, int &lo,
+                                                 int &hi) {
+    lo = hi = 0;
+    const int lane = lane_id();
+    if (lane < E_local) {
+        lo = offsets[lane];
+        hi = offsets[lane + 1];
+        lo = lo < 0 ? 0 : (lo > A_cap ? A_cap : lo);
+        hi = hi < lo ? lo : (hi > A_cap ? A_cap : hi);
+    }
 }
 
 struct RaggedTile {
