@@ -46,7 +46,12 @@ __global__ __launch_bounds__(256) void pack_router_kernel(const float *__restric
 // With 32-token wave tiles a whole chunk is software-pipelined (see PIPE below): operands of
 // sub-tile i in registers, sub-tile i+1 in a ring of three LDS buffers, i+2 on its way from
 // staging registers into LDS, i+3 to i+5 in flight from memory.
-template <bool BF16, int TE, int NWV, int TQ, bool MFMA>
+// ALLCHUNKS (matrix pipe only): the workgroup walks ALL the chunks of its tokens and adds the
+// chunk results up in registers, left to right - the declared order - so that scratch holds one
+// 64-expert vector per token (256 bytes) instead of one per chunk (2 KB at d = 2048, written
+// here and read back by the selection).  For batches with at least one wave tile per SIMD of
+// the chip; smaller batches need the chunks as separate workgroups to fill it.
+template <bool BF16, int TE, int NWV, int TQ, bool MFMA, bool ALLCHUNKS = false>
 __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_partial_kernel(const void *__restrict__ x,
                                                                 const float *__restrict__ W, int ldw,
                                                                 int ep, int64_t T, int d, int nchunk,
@@ -68,7 +73,12 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
     // wave tiles only.
     constexpr bool PIPE = MFMA && TOK == 32;
     constexpr int NBUF = PIPE ? 3 : 2;
-    __shared__ __attribute__((aligned(16))) float Wl[NBUF][KS][EPAD];
+    // Row pitch of the W sub-tile: on the matrix pipe lanes 0-31 read row 2kp and lanes 32-63 row
+    // 2kp+1 of the same 32 columns; with 64-float rows the two halves of the wave would meet in
+    // the same banks (256 bytes apart: a 2-way conflict on every W read, counted), so a 64-wide
+    // row gets 32 floats of padding and the halves land 32 banks apart.
+    constexpr int WPITCH = (MFMA && EPAD == 64) ? EPAD + 32 : EPAD;
+    __shared__ __attribute__((aligned(16))) float Wl[NBUF][KS][WPITCH];
     __shared__ __attribute__((aligned(16))) unsigned char Xl[NBUF][NWV][TOK * XPITCH];
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -77,11 +87,12 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
     const int64_t nwt = ntiles * (64 / TOK);       // wave tiles
     const int64_t ngroups = (nwt + NWV - 1) / NWV;
     const int64_t tgroup = blockIdx.x % ngroups;  // token tiles fastest: neighbours share W rows in L2
-    const int chunk = (int)(blockIdx.x / ngroups);
+    const int chunk_first = ALLCHUNKS ? 0 : (int)(blockIdx.x / ngroups);
+    const int chunk_last = ALLCHUNKS ? nchunk - 1 : chunk_first;
     const int64_t wt = tgroup * NWV + wave;        // may be >= nwt: such a wave only helps load W
     const bool live = wt < nwt;
-    const int k_begin = chunk * C2R_CANON_CHUNK;
-    const int k_end = min(d, k_begin + C2R_CANON_CHUNK);
+    int chunk = chunk_first, k_begin = chunk * C2R_CANON_CHUNK;
+    int k_end = min(d, k_begin + C2R_CANON_CHUNK);
     const int64_t t0 = wt * TOK;
     const unsigned char *xb = static_cast<const unsigned char *>(x);
 
@@ -169,6 +180,7 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
         for (int b = 0; b < NTB; ++b)
 #pragma unroll
             for (int i = 0; i < 16; ++i) macc[a][b][i] = 0.0f;
+    f32x16 mtot[ALLCHUNKS ? NEB : 1][ALLCHUNKS ? NTB : 1];  // sum of the chunks done so far
     const int mh = lane >> 5, mc = lane & 31;  // k parity and block column fed by this lane
     float acc[TQ][TE];
 #pragma unroll
@@ -255,6 +267,11 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
             }
         }
     };
+    for (;; ++chunk) {  // one trip unless ALLCHUNKS
+    if constexpr (ALLCHUNKS) {
+        k_begin = chunk * C2R_CANON_CHUNK;
+        k_end = min(d, k_begin + C2R_CANON_CHUNK);
+    }
     bool piped = false;
     if constexpr (PIPE) {
         // Sub-tile i: operands in registers (set i % 2); sub-tile i+1: in LDS buffer (i+1) % 3;
@@ -349,9 +366,26 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
         __syncthreads();
     }
     }
+    if constexpr (ALLCHUNKS) {
+        // chunk results are added left to right (plain fp32 adds, as the selection kernel does
+        // when it reads them from scratch), and the next chunk starts again from +0
+#pragma unroll
+        for (int a = 0; a < NEB; ++a)
+#pragma unroll
+            for (int b = 0; b < NTB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    mtot[a][b][i] = chunk == 0 ? macc[a][b][i] : mtot[a][b][i] + macc[a][b][i];
+                    macc[a][b][i] = 0.0f;
+                }
+        __syncthreads();  // every wave is done with the LDS buffers before the next chunk refills them
+    }
+    if (chunk >= chunk_last) break;
+    }
     if (!live) return;
     const int64_t tile = wt / (64 / TOK);           // the 64-token tile and this wave's part of it
-    float *dst = part + (((size_t)tile * nchunk + chunk) * ep) * 64 + (wt % (64 / TOK)) * TOK;
+    float *dst = part + (((size_t)tile * (ALLCHUNKS ? 1 : nchunk) + (ALLCHUNKS ? 0 : chunk)) * ep) * 64 +
+                 (wt % (64 / TOK)) * TOK;
     if constexpr (MFMA) {
         // register i of a 32 x 32 block: expert (i/4)*8 + 4*(lane/32) + i%4, token lane%32
 #pragma unroll
@@ -361,7 +395,7 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int e = a * 32 + (i / 4) * 8 + mh * 4 + i % 4;
-                    if (e < ep) dst[(size_t)e * 64 + b * 32 + mc] = macc[a][b][i];
+                    if (e < ep) dst[(size_t)e * 64 + b * 32 + mc] = ALLCHUNKS ? mtot[a][b][i] : macc[a][b][i];
                 }
         return;
     }
@@ -767,19 +801,32 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
     const bool wide = ntiles * L.nchunk >= 2048 && te == 1;
     constexpr int NWV = 4;
     const int64_t nwt = wide ? ntiles : ntiles * 2;
-    const int64_t nblk = (nwt + NWV - 1) / NWV * L.nchunk;
+    // With at least one 32-token wave tile per SIMD of the chip (1024), a workgroup on the matrix
+    // pipe walks all the chunks of its tokens and keeps the running sum in registers: scratch then
+    // holds ONE vector per token instead of one per chunk.  Smaller batches need the chunks as
+    // separate workgroups to fill the chip.
+    const bool all_chunks = !wide && te > 1 && nwt >= 1024 && L.nchunk > 1;
+    const int nchunk_out = all_chunks ? 1 : L.nchunk;
+    const int64_t nblk = (nwt + NWV - 1) / NWV * nchunk_out;
     if (nblk >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     // more than 8 experts: the matrix pipe, a wave covering 32 or 64 experts (columns past the packed
     // expert count re-read column 0; their sums are never stored)
 #define C2R_ROUTE_LAUNCH(BF, TE, NWV, TQ, MF)                                                     \
     route_partial_kernel<BF, TE, NWV, TQ, MF><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(    \
         x, W, ldw, L.EP, T, d, L.nchunk, ntiles, part)
-#define C2R_ROUTE_TE(BF, NWV, TQ)                                 \
-    switch (te) {                                                 \
-        case 8: C2R_ROUTE_LAUNCH(BF, 8, NWV, TQ, true); break;    \
-        case 4: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ, true); break;    \
-        case 2: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ, true); break;    \
-        default: C2R_ROUTE_LAUNCH(BF, 1, NWV, TQ, false); break;  \
+#define C2R_ROUTE_LAUNCH_ALL(BF, TE, NWV, TQ)                                                          \
+    route_partial_kernel<BF, TE, NWV, TQ, true, true><<<dim3((unsigned)nblk), dim3(NWV * 64), 0, st>>>(  \
+        x, W, ldw, L.EP, T, d, L.nchunk, ntiles, part)
+#define C2R_ROUTE_TE(BF, NWV, TQ)                                     \
+    if (all_chunks) {                                                 \
+        if (te == 8) { C2R_ROUTE_LAUNCH_ALL(BF, 8, NWV, TQ); }        \
+        else { C2R_ROUTE_LAUNCH_ALL(BF, 4, NWV, TQ); }                \
+    } else                                                            \
+    switch (te) {                                                     \
+        case 8: C2R_ROUTE_LAUNCH(BF, 8, NWV, TQ, true); break;        \
+        case 4: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ, true); break;        \
+        case 2: C2R_ROUTE_LAUNCH(BF, 4, NWV, TQ, true); break;        \
+        default: C2R_ROUTE_LAUNCH(BF, 1, NWV, TQ, false); break;      \
     }
     if (x_dt == C2R_BF16) {
         if (wide) { C2R_ROUTE_LAUNCH(true, 1, NWV, 8, false); } else { C2R_ROUTE_TE(true, NWV, 4) }
@@ -787,9 +834,10 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
         if (wide) { C2R_ROUTE_LAUNCH(false, 1, NWV, 8, false); } else { C2R_ROUTE_TE(false, NWV, 4) }
     }
 #undef C2R_ROUTE_TE
+#undef C2R_ROUTE_LAUNCH_ALL
 #undef C2R_ROUTE_LAUNCH
     C2R_EP_SWITCH(L.EP, route_select_kernel<EP, false><<<dim3((unsigned)ntiles), dim3(SEL_WAVES * 64), 0, st>>>(
-                            part, L.nchunk, bias, T, E, K, collab_idx, Tc, topk_idx, gates, logits_out));
+                            part, nchunk_out, bias, T, E, K, collab_idx, Tc, topk_idx, gates, logits_out));
     return launch_status();
 }
 

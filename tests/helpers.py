@@ -57,7 +57,11 @@ TOL = {"f32": 1e-5, "bf16": 1e-2}
 # a few times 2^-9 of the magnitude of the TERMS it sums, which for an element that is itself
 # near zero is a few times 2^-9 * rms, i.e. inside 1e-2 * rms but not by a wide margin, so a
 # small share of elements is allowed to land outside.
-SHARE_OUTSIDE_MAX = {"f32": 0.0, "bf16": 1e-3}
+SHARE_OUTSIDE_MAX = {"f32": 0.0, "bf16": 1e-4}     # measured at full size: 6e-8 .. 1e-5
+# Every token's row on its own scale: max |d| over the row / max |ref| over the row.  Measured at
+# full size 7.6e-3 (bf16), 1.5e-6 (fp32): a wrong row (a tile of the ragged map written to the
+# wrong place, a missing term of the combine) is off by order 1.
+ROW_TOL = {"f32": 1e-5, "bf16": 1.5e-2}
 
 
 class OracleLayer:

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 from paper_2504_01337_amd import workloads as wl
-from helpers import GATE_RTOL, OracleLayer, SHARE_OUTSIDE_MAX, TOL, dev, host, max_rel_err, share_outside
+from helpers import GATE_RTOL, OracleLayer, ROW_TOL, SHARE_OUTSIDE_MAX, TOL, dev, host, max_rel_err, share_outside
 
 pytestmark = pytest.mark.gpu
 
@@ -80,6 +80,7 @@ def _run_layer(c2r, orc, w, n_sample):
           f"max {np.nanmax(row_err):.3e}", flush=True)
     assert err <= TOL[w.dtype]
     assert share <= SHARE_OUTSIDE_MAX[w.dtype]
+    assert np.nanmax(row_err) <= ROW_TOL[w.dtype]
     assert torch.isfinite(y.float()).all()
     layer.Cm = Cm
     return layer, o
