@@ -456,7 +456,8 @@ def main():
     stage_info = {}
     route_flops = 2.0 * w.T * w.d * w.E
     route_bytes = w.T * w.d * sz + w.T * w.K * 8 + w.d * w.E * 4
-    stage_info["route"] = {"ms": st_ms["route"], "GBps": route_bytes / st_ms["route"] / 1e6,
+    stage_info["route"] = {"ms": st_ms["route"], "bytes": route_bytes, "flops": route_flops,
+                           "GBps": route_bytes / st_ms["route"] / 1e6,
                            "TFLOPs": route_flops / st_ms["route"] / 1e9,
                            "frac_hbm": route_bytes / st_ms["route"] / 1e6 / PEAK["hbm_GBps"],
                            "frac_valu_f32": route_flops / st_ms["route"] / 1e9 / PEAK["valu_f32_TFLOPs"]}
@@ -466,10 +467,10 @@ def main():
         stage_info["permute"].update({"GBps": perm_bytes / st_ms["permute"] / 1e6,
                                       "frac_hbm": perm_bytes / st_ms["permute"] / 1e6 / PEAK["hbm_GBps"]})
     stage_info["permute_standalone_with_rows"] = {
-        "ms": permute_rows_ms, "GBps": perm_bytes / permute_rows_ms / 1e6,
+        "ms": permute_rows_ms, "bytes": perm_bytes, "GBps": perm_bytes / permute_rows_ms / 1e6,
         "frac_hbm": perm_bytes / permute_rows_ms / 1e6 / PEAK["hbm_GBps"], "in_step": not (L.fuse_gather or L.gather_both)}
     comb_bytes = n_local * w.d * sz + w.T * w.d * sz * (2 if shared else 1) + A * 8
-    stage_info["combine"] = {"ms": st_ms["combine"], "GBps": comb_bytes / st_ms["combine"] / 1e6,
+    stage_info["combine"] = {"ms": st_ms["combine"], "bytes": comb_bytes, "GBps": comb_bytes / st_ms["combine"] / 1e6,
                              "frac_hbm": comb_bytes / st_ms["combine"] / 1e6 / PEAK["hbm_GBps"]}
     fl_gu = 4.0 * n_local * w.d * w.F
     fl_dn = 2.0 * n_local * w.d * w.F
@@ -511,6 +512,23 @@ def main():
             stage_info[name]["frac_groupwise_roof"] = t * 1e3 / st_ms[name]
             stage_info[name]["groups_weight_bound"] = int((nz & (4.0 * cnts * w.d * w.F / peak_fl <
                                                                  (2.0 * w.F * w.d + cnts * (w.d + w.F)) * sz / hbm)).sum())
+    # algorithmic HBM bytes of the FFN launches: every non-empty expert's weights once, activations
+    # read once (x: every token row once, also for the shared expert of the same launch) and
+    # written once
+    n_ne = int(nz.sum())
+    by_gu = n_ne * 2 * w.F * w.d * sz + w.T * w.d * sz + n_local * 4 + n_local * w.F * sz
+    by_dn = n_ne * w.F * w.d * sz + n_local * w.F * sz + n_local * w.d * sz
+    by_sgu = (2 * w.F_shared * w.d * sz + w.T * w.F_shared * sz) if shared else 0
+    by_sdn = (w.F_shared * w.d * sz + w.T * w.F_shared * sz + w.T * w.d * sz) if shared else 0
+    if shared and L.fuse_shared:
+        by_gu, by_dn = by_gu + by_sgu, by_dn + by_sdn
+    elif shared:
+        by_sgu += w.T * w.d * sz
+    for name, nb in (("ffn_gate_up", by_gu), ("ffn_down", by_dn), ("shared_gate_up", by_sgu), ("shared_down", by_sdn)):
+        if name in stage_info:
+            stage_info[name]["bytes"] = nb
+    if "ffn_both_passes" in stage_info:
+        stage_info["ffn_both_passes"]["bytes"] = by_gu + by_dn
     ffn_tf = (fl_gu + fl_dn + fl_sgu + fl_sdn) / ffn_span_ms / 1e9
     stage_info["expert_ffn_all"] = {"ms": ffn_span_ms, "TFLOPs": ffn_tf, "frac_mfma": ffn_tf / PEAK["mfma_bf16_TFLOPs"],
                                     "note": "first FFN launch's start to last one's end; route and permute run inside it"

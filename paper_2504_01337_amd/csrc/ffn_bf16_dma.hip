@@ -71,6 +71,14 @@ __device__ __forceinline__ void wait_copies_and_lds() {
 #endif
 }
 
+// lgkmcnt(0) alone: this wave's LDS reads have returned and its LDS writes are done; whatever
+// it has in flight to or from memory (the epilogue's stores) stays in flight.
+__device__ __forceinline__ void wait_lds_only() {
+#if defined(__HIP_DEVICE_COMPILE__)
+    __builtin_amdgcn_s_waitcnt(0xC07F);
+#endif
+}
+
 // Same, and this wave's LDS reads have returned (lgkmcnt(0)).
 template <int N>
 __device__ __forceinline__ void wait_copies_but_and_lds() {
@@ -117,13 +125,15 @@ __device__ __forceinline__ int xcd_list_slots(int n_tiles) {
 
 // One output tile: position `slot` of XCD `xcd`'s list.  Every wave of the workgroup calls it
 // with the same arguments; it returns early (all waves alike) when the position holds nothing.
-// grp_lo, grp_hi: the row range of this lane's expert of the ragged problem (load_group_range).
+// grp_lo, grp_hi: the row range of this lane's expert of the ragged problem (load_group_range);
+// sg_lo, sg_hi: the row range of the single group (clamped), the same in every lane.
 // before_epilogue(): called once by every wave after the tile's last k-step (the kernel draws
 // the next ticket there, so that the trip to the counter overlaps the epilogue); not called on
 // the early returns.
 template <int MODE, int WM, int WN, class BeforeEpilogue>
 __device__ __forceinline__ void ffn_tile(const FfnLaunchArgs Lp, unsigned char *smem, const int xcd, const int slot,
-                                         const int grp_lo, const int grp_hi, BeforeEpilogue &&before_epilogue) {
+                                         const int grp_lo, const int grp_hi, const int sg_lo, const int sg_hi,
+                                         BeforeEpilogue &&before_epilogue) {
     const FfnLaunchConst &L = *Lp;
     constexpr int BM = 256, BN = 256, BK = 64;
     constexpr int NW = WM * WN;                // waves
@@ -170,19 +180,13 @@ __device__ __forceinline__ void ffn_tile(const FfnLaunchArgs Lp, unsigned char *
     // always-on shared expert).  An XCD's list: its share of the single group's tiles, then of
     // the ragged problem's full tiles, then of its short tiles (ffn_common.h).  One group (a
     // shared expert, a plain GEMM) needs no map: its bounds are two scalars.
-    auto group_bounds = [&](const FfnProblemConst &P, int &lo, int &hi) {
-        lo = P.offsets ? P.offsets[0] : P.row_lo;
-        hi = P.offsets ? P.offsets[1] : P.row_hi;
-        lo = lo < 0 ? 0 : (lo > P.A_cap ? P.A_cap : lo);
-        hi = hi < lo ? lo : (hi > P.A_cap ? P.A_cap : hi);
-    };
     // (the launcher puts the ragged problem, if any, in p[0] and the single group in p[1])
     const bool ragged0 = L.has_ragged != 0, have_sg = L.has_single != 0;
-    int slo = 0, shi = 0, smt = 0;
+    const int slo = sg_lo, shi = sg_hi;
+    int smt = 0;
     XcdRange rs, ra, rb;
     rs.first = rs.cnt = ra.first = ra.cnt = rb.first = rb.cnt = 0;
     if (have_sg) {
-        group_bounds(L.p[1], slo, shi);
         smt = (shi - slo + BM - 1) / BM;
         rs = equal_range(smt * L.p[1].ntn, xcd);
     }
@@ -725,17 +729,20 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
     // lookup is wave-wide arithmetic on them; they do not change during the launch)
     int grp_lo = 0, grp_hi = 0;
     if (L.has_ragged) load_group_range(L.p[0].offsets, L.p[0].E_local, L.p[0].A_cap, grp_lo, grp_hi);
+    // ... and the single group's row range (two scalars)
+    int sg_lo = 0, sg_hi = 0;
+    if (L.has_single) {
+        sg_lo = L.p[1].offsets ? L.p[1].offsets[0] : L.p[1].row_lo;
+        sg_hi = L.p[1].offsets ? L.p[1].offsets[1] : L.p[1].row_hi;
+        sg_lo = sg_lo < 0 ? 0 : (sg_lo > L.p[1].A_cap ? L.p[1].A_cap : sg_lo);
+        sg_hi = sg_hi < sg_lo ? sg_lo : (sg_hi > L.p[1].A_cap ? L.p[1].A_cap : sg_hi);
+        sg_lo = __builtin_amdgcn_readfirstlane(sg_lo);
+        sg_hi = __builtin_amdgcn_readfirstlane(sg_hi);
+    }
     // the first wave works the queues; its lane x < 8 keeps the number of slots of XCD x's list
     int my_len = 0;
     if (tid < 64) {
-        int n_s = 0;
-        if (L.has_single) {
-            int lo = L.p[1].offsets ? L.p[1].offsets[0] : L.p[1].row_lo;
-            int hi = L.p[1].offsets ? L.p[1].offsets[1] : L.p[1].row_hi;
-            lo = lo < 0 ? 0 : (lo > L.p[1].A_cap ? L.p[1].A_cap : lo);
-            hi = hi < lo ? lo : (hi > L.p[1].A_cap ? L.p[1].A_cap : hi);
-            n_s = (hi - lo + S::BM - 1) / S::BM * L.p[1].ntn;
-        }
+        const int n_s = (sg_hi - sg_lo + S::BM - 1) / S::BM * (L.has_single ? L.p[1].ntn : 0);
         int totA = 0, totB = 0;
         if (L.has_ragged) {
             const RaggedMap m = ragged_map_of<S::BM>(grp_lo, grp_hi);
@@ -746,29 +753,46 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
         my_len = xcd_list_slots(equal_range(n_s, x).cnt + equal_range(totA, x).cnt + equal_range(totB, x).cnt);
     }
     int q = home;        // the queue this workgroup draws from: its own XCD's until that is empty
-    int ticket = -1;     // (lane 0 of the first wave) a ticket of queue q drawn ahead, -1: none
-    bool drawn = false;  // a ticket has been drawn ahead
+    // The first position of every workgroup is its own number in its XCD (no trip to the counter
+    // before the first tile); the counters hand out what lies beyond those.
+    int ticket = (int)(blockIdx.x >> 3);  // (lane 0 of the first wave) a ticket of queue q drawn ahead
+    bool drawn = true;                    // such a ticket is at hand
     for (;;) {
         if (tid < 64) {
+            // Every trip ends by checking the ticket it holds, so no valid ticket is ever dropped.
+            // A ticket that comes back past the end of its list (another workgroup was faster) makes
+            // that list look empty from then on, so at most one draw per list fails: 9 trips at most.
             int t = -1;
-            for (int tries = 0; tries < 8; ++tries) {
-                const int len = __builtin_amdgcn_readlane(my_len, q);
-                if (len > 0) {
-                    if (!drawn && lane == 0) ticket = atomicAdd(&queues[q], 1);
-                    drawn = false;
-                    t = __builtin_amdgcn_readfirstlane(ticket);
-                    if (t < len) break;
+            bool have = drawn;  // the ticket drawn during the last epilogue, or the static first one
+            drawn = false;
+            for (int tries = 0; tries < 16; ++tries) {
+                if (!have) {
+                    // Look before drawing: one coherent read of the eight counters tells which lists
+                    // still hold something (counters only grow, so "empty" is final), and a workgroup
+                    // that finds them all empty leaves at once - drawing from eight empty queues one
+                    // after the other cost 15 us at the end of every launch.
+                    const int x = lane & 7;
+                    const int seen = __hip_atomic_load(&queues[x], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) +
+                                     (((int)gridDim.x - x + 7) >> 3);
+                    const uint32_t avail = (uint32_t)__ballot(lane < 8 && seen < my_len) & 0xffu;
+                    if (avail == 0) break;  // (t is -1)
+                    // own XCD's list first, then the next one (cyclically) that holds something
+                    const uint32_t rot = ((avail >> q) | (avail << (8 - q))) & 0xffu;
+                    q = (q + __builtin_ctz(rot)) & 7;
+                    if (lane == 0) ticket = atomicAdd(&queues[q], 1) + (((int)gridDim.x - q + 7) >> 3);
                 }
-                drawn = false;
+                have = false;
+                t = __builtin_amdgcn_readfirstlane(ticket);
+                if (t < __builtin_amdgcn_readlane(my_len, q)) break;
                 t = -1;
-                q = (q + 1) & 7;
             }
             if (lane == 0) {
                 claim[0] = q;
                 claim[1] = t;
             }
         }
-        __syncthreads();  // the claim is visible
+        wait_lds_only();
+        lds_barrier();  // the claim is visible
         q = __builtin_amdgcn_readfirstlane(claim[0]);
         const int slot = __builtin_amdgcn_readfirstlane(claim[1]);
         if (slot < 0) break;  // every queue is empty
@@ -778,19 +802,24 @@ __global__ __launch_bounds__(WM *WN * 64) void ffn_bf16_dma_kernel(const FfnLaun
         FfnLaunchArgs Lp = (FfnLaunchArgs)__builtin_amdgcn_kernarg_segment_ptr();
         asm volatile("" : "+s"(Lp));
         drawn = false;
-        ffn_tile<MODE, WM, WN>(Lp, smem, q, slot, grp_lo, grp_hi, [&]() {
+        ffn_tile<MODE, WM, WN>(Lp, smem, q, slot, grp_lo, grp_hi, sg_lo, sg_hi, [&]() {
             // the next ticket of the same queue, drawn while the epilogue runs
-            if (tid == 0) ticket = atomicAdd(&queues[q], 1);
+            if (tid == 0) ticket = atomicAdd(&queues[q], 1) + (((int)gridDim.x - q + 7) >> 3);
             drawn = true;
         });
-        // this wave's stores have left and its LDS reads have returned (and the ticket is here);
-        // then every wave's: the next claim and the next tile's copies may overwrite the stages
-        wait_copies_and_lds();
-        __syncthreads();
+        // This wave's LDS reads have returned; then every wave's: the next claim and the next tile's
+        // copies may overwrite the stages.  The epilogue's stores are NOT waited for (a workgroup
+        // that ends does not wait for its stores either): they drain while the next tile is looked
+        // up and its first slices are requested.  The copy waits of the next tile stay correct with
+        // stores in flight: they ask for "at most N operations outstanding", copies complete in
+        // order among themselves, so older stores still in flight only make a wait longer.
+        wait_lds_only();
+        lds_barrier();
     }
     // the last workgroup to leave clears the set for the launch that gets it next
+    // (this workgroup's draws have all returned - their values were used - so they precede the
+    // count below; no fence: a device-scope release would write the XCD's whole L2 back)
     if (tid == 0) {
-        __threadfence();
         if (atomicAdd(&queues[8], 1) == (int)gridDim.x - 1) {
             for (int i = 0; i < 9; ++i) atomicExch(&queues[i], 0);
         }
