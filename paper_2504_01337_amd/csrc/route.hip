@@ -73,11 +73,12 @@ __global__ __launch_bounds__(NWV * 64, (MFMA && TQ == 4) ? 2 : 1) void route_par
     // wave tiles only.
     constexpr bool PIPE = MFMA && TOK == 32;
     constexpr int NBUF = PIPE ? 3 : 2;
-    // Row pitch of the W sub-tile: on the matrix pipe lanes 0-31 read row 2kp and lanes 32-63 row
-    // 2kp+1 of the same 32 columns; with 64-float rows the two halves of the wave would meet in
-    // the same banks (256 bytes apart: a 2-way conflict on every W read, counted), so a 64-wide
-    // row gets 32 floats of padding and the halves land 32 banks apart.
-    constexpr int WPITCH = (MFMA && EPAD == 64) ? EPAD + 32 : EPAD;
+    // (Counted on the matrix-pipe form at E = 60: SQ_LDS_BANK_CONFLICT = 128 cycles per wave task of
+    // 8 sub-tiles, i.e. 16 per sub-tile - one per x operand read: 32 token rows 80 bytes apart fall
+    // on 16 banks, a 2-way conflict that any row pitch that keeps the 16-byte staging stores
+    // aligned has.  Against the 2048 matrix-pipe cycles of a sub-tile that is under 1 %; padding
+    // the W rows instead, 32 floats per 64-wide row, changed neither the counter nor the time.)
+    constexpr int WPITCH = EPAD;
     __shared__ __attribute__((aligned(16))) float Wl[NBUF][KS][WPITCH];
     __shared__ __attribute__((aligned(16))) unsigned char Xl[NBUF][NWV][TOK * XPITCH];
 
