@@ -179,7 +179,7 @@ def bench_profiling(args, w, torch, np, c2r, wl):
     co_bytes = T * K * 4
     stages = {"select": {"ms": st_ms["select"], "GBps": sel_bytes / st_ms["select"] / 1e6,
                          "frac_hbm": sel_bytes / st_ms["select"] / 1e6 / PEAK["hbm_GBps"],
-                         "bytes": sel_bytes, "kernel": "route_select_kernel<60, ROWMAJOR>"},
+                         "bytes": sel_bytes, "kernel": "route_select_rows_kernel<4, false>"},
               "zero_C": {"ms": st_ms["zero_C"]},
               "coactivation": {"ms": st_ms["coactivation"], "GBps": co_bytes / st_ms["coactivation"] / 1e6,
                                "frac_hbm": co_bytes / st_ms["coactivation"] / 1e6 / PEAK["hbm_GBps"],
@@ -200,7 +200,7 @@ def bench_profiling(args, w, torch, np, c2r, wl):
                 isolated[name][mode + "_frac_hbm"] = nbytes / us / 1e3 / PEAK["hbm_GBps"]
         step()
         torch.cuda.synchronize()
-    roofline = {"kernel": "route_select_kernel<60, ROWMAJOR> (top-K of stored logits)", "bound": "hbm",
+    roofline = {"kernel": "route_select_rows_kernel<4, false> (top-K of stored logits)", "bound": "hbm",
                 "achieved": sel_bytes / dom_ms / 1e6, "peak": PEAK["hbm_GBps"], "unit": "GB/s",
                 "frac": sel_bytes / dom_ms / 1e6 / PEAK["hbm_GBps"], "traffic": None,
                 "avg_launch_ms": dom_ms, "launches_per_step": 1,

@@ -705,6 +705,263 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
     for (int s = 0; s < K; ++s) gates[(size_t)t * K + s] = gates[(size_t)t * K + s] / den;
 }
 
+// Selection from stored logits [T, E] (the profiling pass of Sec. 3.2 routes 2^20 tokens of stored
+// router outputs), for E a multiple of 4 and K <= 4.  What the kernel has to do is stream the
+// logits, so the arithmetic per token is kept small:
+//  * phase 1: a quad of lanes fetches a token's row, lane `sub` the 16-byte pieces at columns
+//    16 i + 4 sub (64 contiguous bytes per quad and load, every load of a 64-token group in flight
+//    at once), and the values go to LDS transposed, [column][token], the token position XOR-ed with
+//    16 sub so that neither these writes nor the reads of phase 2 meet on a bank.
+//  * phase 2, one lane per token.  A logit becomes an order-preserving integer (-0 counted as +0)
+//    whose low 6 bits are replaced by 63 - column: the largest few of these keys - a chain of one
+//    max and a few med3 per value, no index bookkeeping - are the largest logits WITH their
+//    columns, ties to the lower column, provided the keys' upper 26 bits differ among the ones
+//    kept and the next one below them (then the replaced bits decided nothing).  Without lists the
+//    chain keeps five keys of the E columns: the token's K experts and the guard.  With lists it
+//    keeps two (top-1 and guard), then walks the top-1's collaborator list ONLY (built once per
+//    workgroup from the 64-bit masks, ascending: duplicates, the expert itself and out-of-range
+//    entries are gone) keeping four: Tc visits instead of (K - 1) E.
+//  * A token that fails the proviso, or has a NaN or an infinity among its logits, takes the
+//    literal scan (first one standing unless a later one is strictly larger) for every slot.
+template <int NV, bool LISTS>
+__global__ __launch_bounds__(256) void route_select_rows_kernel(const float *__restrict__ logits, int64_t T, int E, int K,
+                                                                const int32_t *__restrict__ collab_idx, int Tc,
+                                                                int32_t *__restrict__ topk_idx,
+                                                                float *__restrict__ gates, int64_t ngroups) {
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    constexpr int TILE_BYTES = 64 * 64 * 4;  // per wave: [column][token ^ 16 * ((column >> 2) & 3)] floats
+    __shared__ __attribute__((aligned(1024))) unsigned char tile_mem[4 * TILE_BYTES];
+    __shared__ uint64_t mask_tab[LISTS ? C2R_MAX_E : 1];
+    // clist[e][k]: the k-th collaborator c of e (ascending) as the byte offset of its column in a
+    // wave's tile, swizzle term included: c * 256 + 64 * ((c >> 2) & 3)
+    __shared__ __attribute__((aligned(16))) uint16_t clist[LISTS ? C2R_MAX_E * 64 : 4];
+    __shared__ int cnt[LISTS ? C2R_MAX_E : 1];
+    __shared__ int maxcnt;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint64_t all = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
+    auto code_of = [](int c) __attribute__((always_inline)) { return (uint32_t)(c * 256 + ((c >> 2) << 4)); };
+    int nmax = 0;
+    if constexpr (LISTS) {
+        if (tid < C2R_MAX_E) mask_tab[tid] = 0ull;
+        if (tid == 0) maxcnt = 0;
+        for (int i = tid; i < C2R_MAX_E * 64 / 2; i += 256) reinterpret_cast<uint32_t *>(clist)[i] = 0u;
+        __syncthreads();
+        const int n = E * Tc;
+#pragma unroll 4
+        for (int i = tid; i < n; i += 256) {
+            const int v = collab_idx[i], e = i / Tc;
+            if (v >= 0 && v < E && v != e) atomicOr(reinterpret_cast<unsigned long long *>(&mask_tab[e]), 1ull << v);
+        }
+        __syncthreads();
+        if (tid < C2R_MAX_E) {
+            uint64_t m = mask_tab[tid];
+            int n2 = 0;
+            while (m) {
+                clist[tid * 64 + n2++] = (uint16_t)code_of(__ffsll((unsigned long long)m) - 1);
+                m &= m - 1;
+            }
+            cnt[tid] = n2;
+            atomicMax(&maxcnt, n2);
+        }
+        __syncthreads();
+        nmax = __builtin_amdgcn_readfirstlane(maxcnt);
+    }
+
+    constexpr int EMPTY = (int)0x80000000;  // below every key
+    // A 64-token group is one contiguous run of 64 E floats = E / 4 wave-wide 16-byte loads; lane l's
+    // piece of load u holds columns col .. col + 3 of token tok, the same in every group.  Byte offsets
+    // into tile_mem: of that piece's first float (the others follow 256 bytes apart), and of this
+    // lane's token for the reads of phase 2.
+    const int NU = E / 4;  // <= 4 NV
+    uint32_t wr_off[4 * NV];
+#pragma unroll
+    for (int u = 0; u < 4 * NV; ++u) {
+        const int f = u * 256 + lane * 4, tok = (f / E) & 63, col = f - (f / E) * E;
+        wr_off[u] = (uint32_t)(wave * TILE_BYTES) + (((uint32_t)(tok * 4)) ^ code_of(col));
+    }
+    const uint32_t lanebase = (uint32_t)(wave * TILE_BYTES + lane * 4);
+    auto lds_f = [&](uint32_t off) __attribute__((always_inline)) -> float & {
+        return *reinterpret_cast<float *>(tile_mem + off);
+    };
+    // this token's logit of column c (any c, per lane)
+    auto logit_of = [&](int c) __attribute__((always_inline)) { return lds_f(lanebase ^ code_of(c)); };
+    auto key_of = [](float v, int c) __attribute__((always_inline)) {
+        const int b = __float_as_int(v);
+        return ((b ^ ((b >> 31) & 0x7fffffff)) & ~63) | (63 - c);
+    };
+    auto med3 = [](int a, int b, int c) __attribute__((always_inline)) {
+        int d;
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+        return d;
+    };
+
+    // all loads of a 64-token group go out together (a piece past the end of the logits re-reads the start)
+    f32x4 q[4 * NV];
+    auto request = [&](int64_t g) __attribute__((always_inline)) {
+        const int64_t left = T - g * 64;
+        const int nflt = (int)(left < 64 ? left : 64) * E;
+        const float *base = logits + g * 64 * E;
+#pragma unroll
+        for (int u = 0; u < 4 * NV; ++u) {
+            const int f = u * 256 + lane * 4;
+            if (u < 4 * NV - 3 || u < NU)  // (uniform)
+                q[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(base + (f < nflt ? f : 0)));
+        }
+    };
+    const int64_t gstep = (int64_t)gridDim.x * 4;
+    int64_t g = (int64_t)blockIdx.x * 4 + wave;
+    if (g < ngroups) request(g);
+    for (; g < ngroups; g += gstep) {
+        // ---- phase 1: the group's logits into LDS, transposed (-0 stored as +0)
+#pragma unroll
+        for (int u = 0; u < 4 * NV; ++u)
+            if (u < 4 * NV - 3 || u < NU) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) lds_f(wr_off[u] + j * 256) = q[u][j] + 0.0f;
+            }
+        // ... and the next group's go out and fly while phase 2 runs
+        if (g + gstep < ngroups) request(g + gstep);
+        // (the wave's own LDS writes, read back by other lanes of the same wave: LDS operations of a
+        // wave complete in order; the fences keep the compiler from moving them)
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
+        // ---- phase 2: one lane per token
+        const int64_t t = g * 64 + lane;
+        constexpr int NKEEP = LISTS ? 2 : 5;
+        int k[NKEEP];
+#pragma unroll
+        for (int u = 0; u < NKEEP; ++u) k[u] = EMPTY;
+        float chk = 0.0f;
+#pragma unroll
+        for (int c = 0; c < NV * 16; ++c) {
+            if (c < (NV - 1) * 16 || c < E) {  // (uniform)
+                const float v = lds_f((lanebase ^ (uint32_t)((c >> 2) << 4)) + c * 256);
+                chk = __builtin_fmaf(v, 0.0f, chk);  // NaN once a NaN or an infinity went in
+                const int kk = key_of(v, c);
+                int nk[NKEEP];
+                nk[0] = max(k[0], kk);
+#pragma unroll
+                for (int u = 1; u < NKEEP; ++u) nk[u] = med3(k[u - 1], k[u], kk);  // (k[0] >= k[1] >= ... throughout)
+#pragma unroll
+                for (int u = 0; u < NKEEP; ++u) k[u] = nk[u];
+            }
+        }
+        bool literal = chk != chk;
+#pragma unroll
+        for (int u = 0; u + 1 < NKEEP; ++u) literal = literal || !((k[u] >> 6) > (k[u + 1] >> 6) || k[u] == EMPTY);
+        int es[4] = {-1, -1, -1, -1};
+        float vs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        es[0] = 63 - (k[0] & 63);
+        if constexpr (LISTS) {
+            // the top-1's list: four keys kept, the three slots and the guard
+            const int n = cnt[es[0]];
+            const uint16_t *lst = clist + es[0] * 64;
+            int m[4] = {EMPTY, EMPTY, EMPTY, EMPTY};
+            for (int kq = 0; kq < nmax; kq += 4) {
+                const uint2 w = *reinterpret_cast<const uint2 *>(lst + kq);
+                uint32_t code[4] = {w.x & 0xffffu, w.x >> 16, w.y & 0xffffu, w.y >> 16};
+                float v[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) v[j] = lds_f(lanebase ^ code[j]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int kk = kq + j < n ? key_of(v[j], (int)(code[j] >> 8)) : EMPTY;
+                    const int n0 = max(m[0], kk), n1 = med3(m[0], m[1], kk), n2 = med3(m[1], m[2], kk),
+                              n3 = med3(m[2], m[3], kk);
+                    m[0] = n0;
+                    m[1] = n1;
+                    m[2] = n2;
+                    m[3] = n3;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 3; ++u) {
+                literal = literal || !((m[u] >> 6) > (m[u + 1] >> 6) || m[u] == EMPTY);
+                es[u + 1] = m[u] == EMPTY ? -1 : 63 - (m[u] & 63);
+            }
+        } else {
+#pragma unroll
+            for (int u = 1; u < 4; ++u) es[u] = k[u] == EMPTY ? -1 : 63 - (k[u] & 63);
+        }
+        float gs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        float den;
+        if (literal) {
+            // the literal scan, slot by slot (a NaN stands if it is the first allowed expert)
+            auto pick_row = [&](uint64_t mm, int &bi, float &bv) {
+                bi = -1;
+                bv = 0.0f;
+                for (int e = 0; e < E; ++e) {
+                    const float v = logit_of(e);
+                    const bool take = ((mm >> e) & 1ull) != 0 && (bi < 0 || v > bv);
+                    bv = take ? v : bv;
+                    bi = take ? e : bi;
+                }
+            };
+            int e0;
+            float v0;
+            pick_row(all, e0, v0);
+            uint64_t mm = all & ~(1ull << e0);
+            if constexpr (LISTS) mm = mask_tab[e0];
+            es[0] = e0;
+            gs[0] = expf(v0 - v0);
+            den = gs[0];
+#pragma unroll
+            for (int s2 = 1; s2 < 4; ++s2) {
+                es[s2] = -1;
+                if (s2 < K) {
+                    int e;
+                    float v;
+                    pick_row(mm, e, v);
+                    if (e >= 0) {
+                        mm &= ~(1ull << e);
+                        gs[s2] = expf(v - v0);
+                    }
+                    es[s2] = e;
+                    den += gs[s2];
+                }
+            }
+        } else {
+#pragma unroll
+            for (int s2 = 0; s2 < 4; ++s2) vs[s2] = logit_of(es[s2] < 0 ? 0 : es[s2]);
+            gs[0] = expf(vs[0] - vs[0]);
+            den = gs[0];
+#pragma unroll
+            for (int s2 = 1; s2 < 4; ++s2) {
+                if (s2 < K) {
+                    if (es[s2] >= 0) gs[s2] = expf(vs[s2] - vs[0]);
+                    den += gs[s2];
+                } else {
+                    es[s2] = -1;
+                }
+            }
+        }
+#pragma unroll
+        for (int s2 = 0; s2 < 4; ++s2) gs[s2] = gs[s2] / den;
+        if (t < T) {
+            if (K == 4 && ((reinterpret_cast<uintptr_t>(topk_idx) | reinterpret_cast<uintptr_t>(gates)) & 15) == 0) {
+                const i32x4 ev = {es[0], es[1], es[2], es[3]};
+                const f32x4 gv = {gs[0], gs[1], gs[2], gs[3]};
+                __builtin_nontemporal_store(ev, reinterpret_cast<i32x4 *>(topk_idx + (size_t)t * 4));
+                __builtin_nontemporal_store(gv, reinterpret_cast<f32x4 *>(gates + (size_t)t * 4));
+            } else {
+#pragma unroll
+                for (int s2 = 0; s2 < 4; ++s2)
+                    if (s2 < K) {
+                        topk_idx[(size_t)t * K + s2] = es[s2];
+                        gates[(size_t)t * K + s2] = gs[s2];
+                    }
+            }
+        }
+        // the next group's logits overwrite the tile: every lane's reads of it come first
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
 static int check_route_args(int64_t T, int E, int K, const int32_t *collab_idx, int Tc) {
     if (T < 0 || E < 1 || K < 1 || K > E) return C2R_ERR_INVALID_ARG;
     if (collab_idx && Tc < K - 1) return C2R_ERR_INVALID_ARG;
@@ -854,6 +1111,24 @@ extern "C" int c2r_route_from_logits(const float *logits, int64_t T, int E, int 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t nsel = (T + 63) / 64;
     if (nsel >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
+    if (E % 4 == 0 && K <= 4) {
+        // few, long-lived workgroups: each builds the collaborator lists once and then walks its groups
+        const int64_t nblk = (nsel + 3) / 4 < 512 ? (nsel + 3) / 4 : 512;
+        const dim3 grid((unsigned)nblk), block(256);
+#define C2R_ROWS_LAUNCH(NVV)                                                                                       \
+    if (collab_idx)                                                                                                 \
+        route_select_rows_kernel<NVV, true><<<grid, block, 0, st>>>(logits, T, E, K, collab_idx, Tc, topk_idx, gates, nsel); \
+    else                                                                                                            \
+        route_select_rows_kernel<NVV, false><<<grid, block, 0, st>>>(logits, T, E, K, collab_idx, Tc, topk_idx, gates, nsel)
+        switch ((E + 15) / 16) {
+            case 1: C2R_ROWS_LAUNCH(1); break;
+            case 2: C2R_ROWS_LAUNCH(2); break;
+            case 3: C2R_ROWS_LAUNCH(3); break;
+            default: C2R_ROWS_LAUNCH(4); break;
+        }
+#undef C2R_ROWS_LAUNCH
+        return launch_status();
+    }
     const int EPV = ep_of(E);
     C2R_EP_SWITCH(EPV, route_select_kernel<EP, true><<<dim3((unsigned)nsel), dim3(64), 0, st>>>(
                            logits, 1, (const float *)nullptr, T, E, K, collab_idx, Tc, topk_idx, gates,

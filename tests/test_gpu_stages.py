@@ -109,6 +109,46 @@ def test_route_from_logits(c2r, orc, E, K, Tc, T):
         np.testing.assert_allclose(host(gates), g_ref, rtol=GATE_RTOL, atol=1e-7)
 
 
+@pytest.mark.parametrize("E,K,Tc,T", [(4, 1, 0, 100), (4, 4, 3, 777), (20, 2, 5, 1000), (36, 3, 35, 641),
+                                     (52, 3, 2, 300), (60, 4, 16, 4 * 64 * 513 + 5), (8, 4, 7, 140001)])
+def test_route_from_logits_special_values_signed_zeros_and_short_lists(c2r, orc, E, K, Tc, T):
+    # E a multiple of 4 and K <= 4: the quad-per-token kernel.  Values with many ties, signed zeros
+    # (equal as floats: the lower index stands), -inf / +inf / NaN in some rows (those take the literal
+    # scan), lists with duplicates, self and out-of-range entries (fewer usable entries than K - 1),
+    # and enough tokens that a workgroup walks more than one group of 64.
+    rng = np.random.default_rng(E * 100 + K)
+    logits = rng.integers(-3, 4, size=(T, E)).astype(np.float32)
+    logits[rng.random((T, E)) < 0.2] = -0.0
+    logits[1::9] += rng.standard_normal((len(logits[1::9]), E)).astype(np.float32)
+    logits[3::50, rng.integers(0, E)] = -np.inf
+    logits[7::61, rng.integers(0, E)] = np.inf
+    logits[11::73, rng.integers(0, E)] = np.nan
+    logits[13::97] = -np.inf
+    if T > 200:
+        logits[150] = np.nan
+    # (list handed to the library, the same list as the oracle takes it: the oracle's lists hold valid
+    # expert numbers only, so an out-of-range entry - which the library ignores - is given to it as a
+    # repeat of another entry)
+    lists = [(None, None)]
+    if Tc > 0:
+        collab = _collab(E, Tc, 7)
+        lists.append((collab, collab))
+        if Tc - 3 >= K - 1:
+            bad = collab.copy()
+            bad[:, 0] = np.arange(E)          # the expert itself
+            bad[:, 1] = bad[:, 2]             # a duplicate
+            clean = bad.copy()
+            bad[::2, Tc - 1] = E + 5          # out of range
+            bad[1::2, Tc - 1] = -2
+            clean[:, Tc - 1] = clean[:, 2]
+            lists.append((bad, clean))
+    for ci, ci_ref in lists:
+        idx, gates = c2r.route_from_logits(dev(logits), K, None if ci is None else dev(ci))
+        idx_ref, g_ref = orc.route(logits, K, ci_ref)
+        assert np.array_equal(host(idx), idx_ref)
+        np.testing.assert_allclose(host(gates), g_ref, rtol=GATE_RTOL, atol=1e-7, equal_nan=True)
+
+
 def test_route_from_logits_single_expert(c2r, orc):
     # E = 1: every token selects expert 0; its gate is exp(l - l) / sum = 1 for a finite logit and
     # NaN for an infinite or NaN one (the stated gate rule)
