@@ -379,6 +379,15 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     permute_rows_ms = e0.elapsed_time(e1) / args.steps
+    # ... and the same call without the row scatter: the difference is the row-scatter kernel alone
+    for it in range(args.warmup + args.steps):
+        if it == args.warmup:
+            e0.record()
+        c2r.permute(x, L.idx, L.E, L.local_slot, L.E_local, ws=L.ws_perm,
+                    out=(L.counts, L.offsets, L.perm, L.inv_perm, None), rows=False)
+    e1.record()
+    torch.cuda.synchronize()
+    permute_index_ms = e0.elapsed_time(e1) / args.steps
 
     # Sec. 3.4 on one GPU (outside the step): the zero-redundancy send list for a fixed contiguous
     # 4-device map and the two-level combine that goes with it
@@ -469,6 +478,11 @@ def main():
     stage_info["permute_standalone_with_rows"] = {
         "ms": permute_rows_ms, "bytes": perm_bytes, "GBps": perm_bytes / permute_rows_ms / 1e6,
         "frac_hbm": perm_bytes / permute_rows_ms / 1e6 / PEAK["hbm_GBps"], "in_step": not (L.fuse_gather or L.gather_both)}
+    rows_bytes = w.T * w.d * sz + n_local * w.d * sz + A * 4
+    rows_ms = max(permute_rows_ms - permute_index_ms, 1e-6)
+    stage_info["permute_standalone_with_rows"]["row_scatter_kernel"] = {
+        "ms": rows_ms, "how": "the call with the row scatter minus the same call without it (%.4f ms)" % permute_index_ms,
+        "bytes": rows_bytes, "GBps": rows_bytes / rows_ms / 1e6, "frac_hbm": rows_bytes / rows_ms / 1e6 / PEAK["hbm_GBps"]}
     comb_bytes = n_local * w.d * sz + w.T * w.d * sz * (2 if shared else 1) + A * 8
     stage_info["combine"] = {"ms": st_ms["combine"], "bytes": comb_bytes, "GBps": comb_bytes / st_ms["combine"] / 1e6,
                              "frac_hbm": comb_bytes / st_ms["combine"] / 1e6 / PEAK["hbm_GBps"]}
@@ -611,6 +625,14 @@ def main():
             isolated.setdefault("permute_standalone_with_rows", {})[mode + "_us"] = us
             isolated["permute_standalone_with_rows"][mode + "_GBps"] = perm_bytes / us / 1e3
             isolated["permute_standalone_with_rows"][mode + "_frac_hbm"] = perm_bytes / us / 1e3 / PEAK["hbm_GBps"]
+            us_idx = cold.time(lambda: None, lambda: c2r.permute(x, L.idx, L.E, L.local_slot, L.E_local, ws=L.ws_perm,
+                               out=(L.counts, L.offsets, L.perm, L.inv_perm, None), rows=False), n_it, mode)
+            us_rows = max(us - us_idx, 1e-3)
+            isolated["permute_standalone_with_rows"][mode + "_row_scatter_kernel_us"] = us_rows
+            isolated["permute_standalone_with_rows"][mode + "_row_scatter_kernel_frac_hbm"] = \
+                rows_bytes / us_rows / 1e3 / PEAK["hbm_GBps"]
+            isolated["permute_standalone_with_rows"][mode + "_row_scatter_kernel_frac_of_copy"] = \
+                (rows_bytes / us_rows / 1e3) / isolated["device_copy_192MB"][mode]["GBps"]
 
     input_hashes = None
     if args.hash_inputs:

@@ -263,29 +263,60 @@ __global__ __launch_bounds__(PE_WAVES * 64) void permute_by_slot_kernel(
     }
 }
 
-// One wave per token; row bytes must be a multiple of 16.
+// One wave per token; row bytes must be a multiple of 16.  The token's K positions are fetched
+// first, all at once (they are one 16-byte vector for K = 4), then the row is read in pieces of
+// 4 KB - four loads per lane in flight together, unconditional on clamped indices when the piece is
+// whole - and every piece goes out to the K positions with stores that bypass the caches' keep
+// policy (each output row is written once and read by another kernel).
 __global__ __launch_bounds__(256) void permute_rows_kernel(const uint4 *__restrict__ x, int64_t T, int K,
                                                            int row_vecs,
                                                            const int32_t *__restrict__ inv_perm,
                                                            uint4 *__restrict__ x_perm) {
+    typedef int i32x4 __attribute__((ext_vector_type(4)));
+    typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
     const int lane = threadIdx.x & 63;
     const int64_t t = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (t >= T) return;
+    const u32x4 *src = reinterpret_cast<const u32x4 *>(x) + t * row_vecs;
+    u32x4 *out = reinterpret_cast<u32x4 *>(x_perm);
+    if (K == 4 && (reinterpret_cast<uintptr_t>(inv_perm) & 15) == 0) {
+        const i32x4 pos = *reinterpret_cast<const i32x4 *>(inv_perm + t * 4);
+        if ((pos[0] & pos[1] & pos[2] & pos[3]) < 0) return;  // (all four negative: the token goes nowhere)
+        for (int v0 = 0; v0 < row_vecs; v0 += 256) {
+            u32x4 r[4];
+            const bool whole = v0 + 256 <= row_vecs;  // (uniform)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int v = v0 + i * 64 + lane;
+                r[i] = __builtin_nontemporal_load(src + (whole || v < row_vecs ? v : 0));
+            }
+#pragma unroll
+            for (int s = 0; s < 4; ++s) {
+                if (pos[s] < 0) continue;
+                u32x4 *dst = out + (int64_t)pos[s] * row_vecs;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int v = v0 + i * 64 + lane;
+                    if (whole || v < row_vecs) __builtin_nontemporal_store(r[i], dst + v);
+                }
+            }
+        }
+        return;
+    }
     bool any = false;
     for (int s = 0; s < K; ++s) any |= inv_perm[t * K + s] >= 0;
     if (!any) return;
-    const uint4 *src = x + t * row_vecs;
     for (int v0 = 0; v0 < row_vecs; v0 += 256) {
-        uint4 r[4];
+        u32x4 r[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const int v = v0 + i * 64 + lane;
-            if (v < row_vecs) r[i] = src[v];
+            r[i] = src[v < row_vecs ? v : 0];
         }
         for (int s = 0; s < K; ++s) {
             const int32_t p = inv_perm[t * K + s];
             if (p < 0) continue;
-            uint4 *dst = x_perm + (int64_t)p * row_vecs;
+            u32x4 *dst = out + (int64_t)p * row_vecs;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int v = v0 + i * 64 + lane;
