@@ -124,8 +124,9 @@ class ColdTimer:
 
 def bench_profiling(args, w, torch, np, c2r, wl):
     """Workload C4: the offline profiling of Sec. 3.2 / Sec. 3.3 step 1 on a stored logit stream.
-    A step = conventional top-K of every token (c2r_route_from_logits) -> co-activation matrix
-    (Eq. 2, c2r_build_coactivation into a zeroed C) -> collaborator lists (Eq. 4, c2r_collaborators)."""
+    A step = C zeroed -> conventional top-K of every token and its pair counts (Eq. 2) in one launch
+    (c2r_profile_from_logits; the selections themselves are not written) -> collaborator lists (Eq. 4,
+    c2r_collaborators).  --separate-count runs c2r_route_from_logits and c2r_build_coactivation instead."""
     t_gen = time.time()
     lg_h = wl.direct_logits(w)
     lg = torch.from_numpy(lg_h).cuda()
@@ -138,7 +139,9 @@ def bench_profiling(args, w, torch, np, c2r, wl):
     torch.cuda.synchronize()
     t_gen = time.time() - t_gen
     mk = lambda: torch.cuda.Event(enable_timing=True)
-    names = ("select", "zero_C", "coactivation", "collaborators")
+    fused = not args.separate_count
+    names = ("zero_C", "select_and_count", "collaborators") if fused else ("select", "zero_C", "coactivation", "collaborators")
+    dom = "select_and_count" if fused else "select"
 
     def step(tr=None):
         def run(name, fn):
@@ -147,9 +150,13 @@ def bench_profiling(args, w, torch, np, c2r, wl):
             fn()
             if tr is not None and name in tr:
                 tr[name][1].record()
-        run("select", lambda: c2r.route_from_logits(lg, K, None, out=(idx, gates)))
-        run("zero_C", lambda: Cm.zero_())
-        run("coactivation", lambda: c2r.build_coactivation(idx, E, Cm))
+        if fused:   # one launch selects and counts; the selections themselves are not written
+            run("zero_C", lambda: Cm.zero_())
+            run("select_and_count", lambda: c2r.profile_from_logits(lg, K, Cm))
+        else:
+            run("select", lambda: c2r.route_from_logits(lg, K, None, out=(idx, gates)))
+            run("zero_C", lambda: Cm.zero_())
+            run("coactivation", lambda: c2r.build_coactivation(idx, E, Cm))
         run("collaborators", lambda: c2r.collaborators(Cm, Tc, out=lists))
 
     t_ramp, ramp_steps = time.perf_counter(), 0
@@ -161,36 +168,65 @@ def bench_profiling(args, w, torch, np, c2r, wl):
     for _ in range(args.warmup):
         step()
     ev_every = 4 if args.steps >= 8 else 1
-    ev_dom = [{"select": (mk(), mk())} if i % ev_every == 0 else None for i in range(args.steps)]
+    ev_dom = [{dom: (mk(), mk())} if i % ev_every == 0 else None for i in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
         step(ev_dom[i])
     torch.cuda.synchronize()
     ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
-    dom_ms = float(np.mean([e["select"][0].elapsed_time(e["select"][1]) for e in ev_dom if e is not None]))
+    dom_ms = float(np.mean([e[dom][0].elapsed_time(e[dom][1]) for e in ev_dom if e is not None]))
     ev = [{n: (mk(), mk()) for n in names} for _ in range(args.steps)]
     for i in range(args.steps):
         step(ev[i])
     torch.cuda.synchronize()
     st_ms = {n: float(np.mean([e[n][0].elapsed_time(e[n][1]) for e in ev])) for n in names}
-    # algorithmic bytes: the logits are read once, indices and gates written, the indices read again
+    # algorithmic bytes.  Separate calls: the logits are read once, indices and gates written, the
+    # indices read again by the counting kernel.  Fused: the logits are read once, nothing else moves.
     sel_bytes = T * (E * 4 + K * 8)
     co_bytes = T * K * 4
-    stages = {"select": {"ms": st_ms["select"], "GBps": sel_bytes / st_ms["select"] / 1e6,
-                         "frac_hbm": sel_bytes / st_ms["select"] / 1e6 / PEAK["hbm_GBps"],
-                         "bytes": sel_bytes, "kernel": "route_select_rows_kernel<4, false>"},
-              "zero_C": {"ms": st_ms["zero_C"]},
-              "coactivation": {"ms": st_ms["coactivation"], "GBps": co_bytes / st_ms["coactivation"] / 1e6,
-                               "frac_hbm": co_bytes / st_ms["coactivation"] / 1e6 / PEAK["hbm_GBps"],
-                               "bytes": co_bytes, "increments_per_token": K * K, "kernel": "coactivation_kernel"},
-              "collaborators": {"ms": st_ms["collaborators"], "bound": "latency (60 x 60 integers)"}}
+    fused_bytes = T * E * 4
+    # the calls of the other form, timed back to back outside the step, for the table
+    def loop_ms(fn, n=10):
+        a, b = mk(), mk()
+        fn()
+        a.record()
+        for _ in range(n):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / n
+    if fused:
+        dom_bytes, dom_kernel = fused_bytes, "route_select_rows_kernel<4, false, true>"
+        stages = {"zero_C": {"ms": st_ms["zero_C"]},
+                  "select_and_count": {"ms": st_ms[dom], "GBps": fused_bytes / st_ms[dom] / 1e6,
+                                       "frac_hbm": fused_bytes / st_ms[dom] / 1e6 / PEAK["hbm_GBps"], "bytes": fused_bytes,
+                                       "increments_per_token": K * (K + 1) // 2, "kernel": dom_kernel},
+                  "collaborators": {"ms": st_ms["collaborators"], "bound": "latency (60 x 60 integers)"}}
+        sel_ms = loop_ms(lambda: c2r.route_from_logits(lg, K, None, out=(idx, gates)))
+        co_ms = loop_ms(lambda: c2r.build_coactivation(idx, E, Cm))
+        stages["separate_calls_outside_the_step"] = {
+            "select": {"ms": sel_ms, "bytes": sel_bytes, "GBps": sel_bytes / sel_ms / 1e6,
+                       "frac_hbm": sel_bytes / sel_ms / 1e6 / PEAK["hbm_GBps"], "kernel": "route_select_rows_kernel<4, false, false>"},
+            "coactivation": {"ms": co_ms, "bytes": co_bytes, "GBps": co_bytes / co_ms / 1e6,
+                             "frac_hbm": co_bytes / co_ms / 1e6 / PEAK["hbm_GBps"], "kernel": "coactivation_kernel<16>"}}
+    else:
+        dom_bytes, dom_kernel = sel_bytes, "route_select_rows_kernel<4, false, false>"
+        stages = {"select": {"ms": st_ms["select"], "GBps": sel_bytes / st_ms["select"] / 1e6,
+                             "frac_hbm": sel_bytes / st_ms["select"] / 1e6 / PEAK["hbm_GBps"],
+                             "bytes": sel_bytes, "kernel": dom_kernel},
+                  "zero_C": {"ms": st_ms["zero_C"]},
+                  "coactivation": {"ms": st_ms["coactivation"], "GBps": co_bytes / st_ms["coactivation"] / 1e6,
+                                   "frac_hbm": co_bytes / st_ms["coactivation"] / 1e6 / PEAK["hbm_GBps"],
+                                   "bytes": co_bytes, "increments_per_token": K * (K + 1) // 2, "kernel": "coactivation_kernel<16>"},
+                  "collaborators": {"ms": st_ms["collaborators"], "bound": "latency (60 x 60 integers)"}}
     isolated = None
     if args.isolate:
         cold = ColdTimer(torch)
         n_it = max(3, min(args.steps, 8))
         isolated = {"device_copy_192MB": cold.copy_yardstick(n_it)}
-        for name, fn, nbytes in (("select", lambda: c2r.route_from_logits(lg, K, None, out=(idx, gates)), sel_bytes),
+        for name, fn, nbytes in (("select_and_count", lambda: c2r.profile_from_logits(lg, K, Cm), fused_bytes),
+                                 ("select", lambda: c2r.route_from_logits(lg, K, None, out=(idx, gates)), sel_bytes),
                                  ("coactivation", lambda: c2r.build_coactivation(idx, E, Cm), co_bytes)):
             isolated[name] = {}
             for mode in ("after_write", "after_read"):
@@ -200,12 +236,13 @@ def bench_profiling(args, w, torch, np, c2r, wl):
                 isolated[name][mode + "_frac_hbm"] = nbytes / us / 1e3 / PEAK["hbm_GBps"]
         step()
         torch.cuda.synchronize()
-    roofline = {"kernel": "route_select_rows_kernel<4, false> (top-K of stored logits)", "bound": "hbm",
-                "achieved": sel_bytes / dom_ms / 1e6, "peak": PEAK["hbm_GBps"], "unit": "GB/s",
-                "frac": sel_bytes / dom_ms / 1e6 / PEAK["hbm_GBps"], "traffic": None,
+    roofline = {"kernel": dom_kernel + (" (top-K of stored logits and Eq. 2 counts in one launch)" if fused
+                                        else " (top-K of stored logits)"), "bound": "hbm",
+                "achieved": dom_bytes / dom_ms / 1e6, "peak": PEAK["hbm_GBps"], "unit": "GB/s",
+                "frac": dom_bytes / dom_ms / 1e6 / PEAK["hbm_GBps"], "traffic": None,
                 "avg_launch_ms": dom_ms, "launches_per_step": 1,
                 "launches_timed": sum(1 for e in ev_dom if e is not None),
-                "algorithmic_bytes_per_launch": sel_bytes,
+                "algorithmic_bytes_per_launch": dom_bytes,
                 "note": "the 252 MB logit stream fits the 256 MB memory-side cache, so back-to-back steps read part "
                         "of it from there; stages_from_cold_memory has the same launch from cold memory",
                 "timed_by": "event pairs on the launch stream around every fourth step's launch"}
@@ -222,10 +259,14 @@ def bench_profiling(args, w, torch, np, c2r, wl):
         ig, _ = c2r.route_from_logits(lg[:n].contiguous(), K, None)
         Cg = c2r.build_coactivation(ig, E)
         lg_lists, _ = c2r.collaborators(Cg, Tc)
+        # ... and the one-launch form on the same stream
+        Cf, _, _ = c2r.profile_from_logits(lg[:n].contiguous(), K, torch.zeros_like(Cg))
         cpu = {"value": n / tc, "unit": "tokens/s", "cores": orc.num_threads(), "kind": "oracle",
                "sample": f"first {n} tokens of the logit stream through top-K, Eq. 2 and Eq. 4, {tc:.1f} s",
                "indices_bit_exact": bool(np.array_equal(ig.cpu().numpy(), idx_o)),
                "C_bit_exact": bool(np.array_equal(Cg.cpu().numpy().astype(np.int64), np.asarray(C_o, dtype=np.int64))),
+               "C_of_the_one_launch_form_bit_exact": bool(np.array_equal(Cf.cpu().numpy().astype(np.int64),
+                                                                         np.asarray(C_o, dtype=np.int64))),
                "lists_bit_exact": bool(np.array_equal(lg_lists.cpu().numpy(), lists_o))}
     out = {"metric": "C2R profiling tokens/sec (stored logits -> top-K -> co-activation -> collaborator lists)",
            "value": T / (ms_per_step * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
@@ -247,6 +288,8 @@ def main():
     ap.add_argument("--ramp-ms", type=float, default=300.0,
                     help="run the step for this long before the warm-up steps: from idle the chip takes ~50 ms "
                          "under load to settle its clocks, and steps inside that ramp run 5-15 %% slower")
+    ap.add_argument("--separate-count", action="store_true",
+                    help="C4: selection and co-activation counting as two calls (selections written and read back)")
     ap.add_argument("--workload", default="C3",
                     help="C1|C2|C3|C5 (C3 = Qwen1.5-MoE-A2.7B-shaped layer) or C4 (profiling only: stored "
                          "logits -> top-K -> co-activation matrix -> collaborator lists)")

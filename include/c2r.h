@@ -141,6 +141,24 @@ int c2r_route_from_logits(const float *logits, int64_t T, int E, int K, const in
                           int Tc, int32_t *topk_idx, float *gates, void *stream);
 
 /*
+ * The profiling pass of Sec. 3.2 in one launch: c2r_route_from_logits followed by
+ * c2r_build_coactivation (Eq. 2) on its selections, i.e. C[i, j] += the number of these T
+ * tokens whose selected experts include both i and j (diagonal included).  Exact integer counts,
+ * independent of the order of execution; the same results as the two calls in a row.
+ * logits   : fp32[T, E], 16-byte aligned
+ * topk_idx : int32[T, K] out, or NULL
+ * gates    : fp32[T, K] out, or NULL   (a pass that only wants the counts passes NULL for both:
+ *            they may be NULL when E is a multiple of 4 and K <= 4, the shapes the fused kernel
+ *            covers; other shapes run the two kernels one after the other and need both
+ *            arrays: C2R_ERR_UNSUPPORTED without them)
+ * C        : int32[E, E], accumulated into (the caller zeroes it before the first batch); the
+ *            int32 ceiling of c2r_build_coactivation applies
+ * Errors as c2r_route_from_logits; C == NULL -> C2R_ERR_INVALID_ARG.
+ */
+int c2r_profile_from_logits(const float *logits, int64_t T, int E, int K, const int32_t *collab_idx,
+                            int Tc, int32_t *topk_idx, float *gates, int32_t *C, void *stream);
+
+/*
  * Token dispatch on one device (the step the paper inherits from dropless MoE
  * frameworks, Sec. 2 / Sec. 3.1): a stable sort of the assignments
  * a = t*K + s by local expert slot, and the gather of their rows.

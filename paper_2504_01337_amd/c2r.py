@@ -22,7 +22,7 @@ _ERRNAMES = {-1: "C2R_ERR_INVALID_ARG", -2: "C2R_ERR_UNSUPPORTED", -3: "C2R_ERR_
              -4: "C2R_ERR_LAUNCH"}
 
 EXPORTS = ["c2r_version", "c2r_route_chunk", "c2r_workspace_bytes", "c2r_build_coactivation",
-           "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_permute", "c2r_permute_noalloc", "c2r_expert_ffn",
+           "c2r_collaborators", "c2r_route", "c2r_route_from_logits", "c2r_profile_from_logits", "c2r_permute", "c2r_permute_noalloc", "c2r_expert_ffn",
            "c2r_expert_ffn_gate_up", "c2r_expert_ffn_gate_up_gather", "c2r_expert_ffn_gather", "c2r_expert_ffn_down",
            "c2r_expert_ffn_gate_up_with_shared", "c2r_expert_ffn_down_with_shared", "c2r_combine",
            "c2r_place_experts", "c2r_dedup_dispatch", "c2r_combine_partial", "c2r_combine_copies",
@@ -55,6 +55,7 @@ def lib():
         L.c2r_collaborators.argtypes = [vp, i32, i32, vp, vp, vp]
         L.c2r_route.argtypes = [vp, i32, vp, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, sz, vp]
         L.c2r_route_from_logits.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp]
+        L.c2r_profile_from_logits.argtypes = [vp, i64, i32, i32, vp, i32, vp, vp, vp, vp]
         L.c2r_permute.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp, sz, vp]
         L.c2r_permute_noalloc.argtypes = [vp, i32, vp, i64, i32, i32, i32, vp, i32, vp, vp, vp, vp, vp, vp]
         L.c2r_expert_ffn.argtypes = [vp, i32, vp, i32, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
@@ -173,6 +174,23 @@ def route_from_logits(logits, K, collab_idx=None, out=None):
     _check("c2r_route_from_logits", lib().c2r_route_from_logits(_ptr(logits), T, E, K, _ptr(collab_idx), Tc,
                                                                  _ptr(idx), _ptr(gates), _stream()))
     return idx, gates
+
+
+def profile_from_logits(logits, K, Cm, collab_idx=None, out=None, want_selection=False):
+    """Selection from stored logits and co-activation counts (added to Cm, int32[E, E]) in one launch.
+    out = (topk_idx, gates) to have the selections written as well (or want_selection=True to have
+    them allocated); returns (Cm, topk_idx or None, gates or None)."""
+    T, E = logits.shape
+    idx = gates = None
+    if out is not None:
+        idx, gates = out
+    elif want_selection:
+        idx = torch.empty((T, K), dtype=torch.int32, device=logits.device)
+        gates = torch.empty((T, K), dtype=torch.float32, device=logits.device)
+    Tc = 0 if collab_idx is None else collab_idx.shape[1]
+    _check("c2r_profile_from_logits", lib().c2r_profile_from_logits(_ptr(logits), T, E, K, _ptr(collab_idx), Tc,
+                                                                     _ptr(idx), _ptr(gates), _ptr(Cm), _stream()))
+    return Cm, idx, gates
 
 
 def permute(x, topk_idx, E, local_slot=None, E_local=None, ws=None, out=None, rows=True):

@@ -723,11 +723,15 @@ __global__ __launch_bounds__(ROWMAJOR ? 64 : SEL_WAVES * 64) void route_select_k
 //    entries are gone) keeping four: Tc visits instead of (K - 1) E.
 //  * A token that fails the proviso, or has a NaN or an infinity among its logits, takes the
 //    literal scan (first one standing unless a later one is strictly larger) for every slot.
-template <int NV, bool LISTS>
+// COUNT: the token's expert pairs are added to the co-activation matrix (Eq. 2) on the spot - an LDS
+// histogram per workgroup as in coact.hip, one integer atomic per entry at the end - and either
+// output may be left out (null): the profiling pass wants the counts, not the selections.
+template <int NV, bool LISTS, bool COUNT>
 __global__ __launch_bounds__(256) void route_select_rows_kernel(const float *__restrict__ logits, int64_t T, int E, int K,
                                                                 const int32_t *__restrict__ collab_idx, int Tc,
                                                                 int32_t *__restrict__ topk_idx,
-                                                                float *__restrict__ gates, int64_t ngroups) {
+                                                                float *__restrict__ gates, int32_t *__restrict__ Cmat,
+                                                                int64_t ngroups) {
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     typedef int i32x4 __attribute__((ext_vector_type(4)));
     constexpr int TILE_BYTES = 64 * 64 * 4;  // per wave: [column][token ^ 16 * ((column >> 2) & 3)] floats
@@ -738,11 +742,16 @@ __global__ __launch_bounds__(256) void route_select_rows_kernel(const float *__r
     __shared__ __attribute__((aligned(16))) uint16_t clist[LISTS ? C2R_MAX_E * 64 : 4];
     __shared__ int cnt[LISTS ? C2R_MAX_E : 1];
     __shared__ int maxcnt;
+    __shared__ int32_t red[COUNT ? C2R_MAX_E * C2R_MAX_E : 1];  // co-activation counts of this workgroup, red[a][b], a <= b
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint64_t all = E >= 64 ? ~0ull : ((1ull << E) - 1ull);
     auto code_of = [](int c) __attribute__((always_inline)) { return (uint32_t)(c * 256 + ((c >> 2) << 4)); };
     int nmax = 0;
+    if constexpr (COUNT) {
+        for (int i = tid; i < C2R_MAX_E * C2R_MAX_E; i += 256) red[i] = 0;
+        if constexpr (!LISTS) __syncthreads();
+    }
     if constexpr (LISTS) {
         if (tid < C2R_MAX_E) mask_tab[tid] = 0ull;
         if (tid == 0) maxcnt = 0;
@@ -821,7 +830,8 @@ __global__ __launch_bounds__(256) void route_select_rows_kernel(const float *__r
 #pragma unroll
                 for (int j = 0; j < 4; ++j) lds_f(wr_off[u] + j * 256) = q[u][j] + 0.0f;
             }
-        // ... and the next group's go out and fly while phase 2 runs
+        // ... and the next group's go out and fly while phase 2 runs (two groups of a wave in flight,
+        // with a second register set and the loop body twice, measured slower: 72 against 65 us)
         if (g + gstep < ngroups) request(g + gstep);
         // (the wave's own LDS writes, read back by other lanes of the same wave: LDS operations of a
         // wave complete in order; the fences keep the compiler from moving them)
@@ -888,7 +898,7 @@ __global__ __launch_bounds__(256) void route_select_rows_kernel(const float *__r
             for (int u = 1; u < 4; ++u) es[u] = k[u] == EMPTY ? -1 : 63 - (k[u] & 63);
         }
         float gs[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-        float den;
+        float den = 1.0f;
         if (literal) {
             // the literal scan, slot by slot (a NaN stands if it is the first allowed expert)
             auto pick_row = [&](uint64_t mm, int &bi, float &bv) {
@@ -926,39 +936,75 @@ __global__ __launch_bounds__(256) void route_select_rows_kernel(const float *__r
             }
         } else {
 #pragma unroll
-            for (int s2 = 0; s2 < 4; ++s2) vs[s2] = logit_of(es[s2] < 0 ? 0 : es[s2]);
-            gs[0] = expf(vs[0] - vs[0]);
-            den = gs[0];
+            for (int s2 = 1; s2 < 4; ++s2)
+                if (s2 >= K) es[s2] = -1;
+            if (gates) {  // (uniform)
 #pragma unroll
-            for (int s2 = 1; s2 < 4; ++s2) {
-                if (s2 < K) {
-                    if (es[s2] >= 0) gs[s2] = expf(vs[s2] - vs[0]);
-                    den += gs[s2];
-                } else {
-                    es[s2] = -1;
-                }
+                for (int s2 = 0; s2 < 4; ++s2) vs[s2] = logit_of(es[s2] < 0 ? 0 : es[s2]);
+                gs[0] = expf(vs[0] - vs[0]);
+                den = gs[0];
+#pragma unroll
+                for (int s2 = 1; s2 < 4; ++s2)
+                    if (s2 < K) {
+                        if (es[s2] >= 0) gs[s2] = expf(vs[s2] - vs[0]);
+                        den += gs[s2];
+                    }
             }
         }
-#pragma unroll
-        for (int s2 = 0; s2 < 4; ++s2) gs[s2] = gs[s2] / den;
         if (t < T) {
-            if (K == 4 && ((reinterpret_cast<uintptr_t>(topk_idx) | reinterpret_cast<uintptr_t>(gates)) & 15) == 0) {
-                const i32x4 ev = {es[0], es[1], es[2], es[3]};
-                const f32x4 gv = {gs[0], gs[1], gs[2], gs[3]};
-                __builtin_nontemporal_store(ev, reinterpret_cast<i32x4 *>(topk_idx + (size_t)t * 4));
-                __builtin_nontemporal_store(gv, reinterpret_cast<f32x4 *>(gates + (size_t)t * 4));
-            } else {
+            const bool vec = K == 4 && ((reinterpret_cast<uintptr_t>(topk_idx) | reinterpret_cast<uintptr_t>(gates)) & 15) == 0;
+            if (topk_idx) {
+                if (vec) {
+                    const i32x4 ev = {es[0], es[1], es[2], es[3]};
+                    __builtin_nontemporal_store(ev, reinterpret_cast<i32x4 *>(topk_idx + (size_t)t * 4));
+                } else {
+#pragma unroll
+                    for (int s2 = 0; s2 < 4; ++s2)
+                        if (s2 < K) topk_idx[(size_t)t * K + s2] = es[s2];
+                }
+            }
+            if (gates) {
+#pragma unroll
+                for (int s2 = 0; s2 < 4; ++s2) gs[s2] = gs[s2] / den;
+                if (vec) {
+                    const f32x4 gv = {gs[0], gs[1], gs[2], gs[3]};
+                    __builtin_nontemporal_store(gv, reinterpret_cast<f32x4 *>(gates + (size_t)t * 4));
+                } else {
+#pragma unroll
+                    for (int s2 = 0; s2 < 4; ++s2)
+                        if (s2 < K) gates[(size_t)t * K + s2] = gs[s2];
+                }
+            }
+            if constexpr (COUNT) {
+                // Eq. 2: one count for every pair a <= b of the token's experts, the diagonal included,
+                // into the workgroup's histogram (upper triangle)
+                uint64_t ma = 0;
 #pragma unroll
                 for (int s2 = 0; s2 < 4; ++s2)
-                    if (s2 < K) {
-                        topk_idx[(size_t)t * K + s2] = es[s2];
-                        gates[(size_t)t * K + s2] = gs[s2];
+                    if (es[s2] >= 0) ma |= 1ull << es[s2];
+                while (ma) {
+                    const int ea = __ffsll((unsigned long long)ma) - 1;
+                    uint64_t mb = ma;
+                    ma &= ma - 1;
+                    while (mb) {
+                        const int eb = __ffsll((unsigned long long)mb) - 1;
+                        mb &= mb - 1;
+                        atomicAdd(&red[ea * C2R_MAX_E + eb], 1);
                     }
+                }
             }
         }
         // the next group's logits overwrite the tile: every lane's reads of it come first
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
+    }
+    if constexpr (COUNT) {
+        __syncthreads();
+        for (int i = tid; i < E * E; i += 256) {
+            const int r = i / E, c = i - r * E;
+            const int32_t v = red[(r < c ? r : c) * C2R_MAX_E + (r < c ? c : r)];
+            if (v) atomicAdd(&Cmat[i], v);
+        }
     }
 }
 
@@ -1099,6 +1145,47 @@ extern "C" int c2r_route(const void *x, c2r_dtype x_dt, const float *Wg, const f
     return launch_status();
 }
 
+// Selection from stored logits; with Cmat the tokens' expert pairs are counted as well (then topk_idx
+// and gates may be null where the fused kernel runs: E a multiple of 4, K <= 4).
+static int route_from_logits_impl(const float *logits, int64_t T, int E, int K, const int32_t *collab_idx, int Tc,
+                                  int32_t *topk_idx, float *gates, int32_t *Cmat, hipStream_t st) {
+    const int64_t nsel = (T + 63) / 64;
+    if (nsel >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
+    if (E % 4 == 0 && K <= 4) {
+        // few, long-lived workgroups: each builds the collaborator lists once and then walks its groups
+        const int64_t nblk = (nsel + 3) / 4 < 512 ? (nsel + 3) / 4 : 512;
+        const dim3 grid((unsigned)nblk), block(256);
+#define C2R_ROWS_ARGS logits, T, E, K, collab_idx, Tc, topk_idx, gates, Cmat, nsel
+#define C2R_ROWS_LAUNCH(NVV)                                                               \
+    if (Cmat) {                                                                            \
+        if (collab_idx)                                                                    \
+            route_select_rows_kernel<NVV, true, true><<<grid, block, 0, st>>>(C2R_ROWS_ARGS);   \
+        else                                                                               \
+            route_select_rows_kernel<NVV, false, true><<<grid, block, 0, st>>>(C2R_ROWS_ARGS);  \
+    } else if (collab_idx)                                                                 \
+        route_select_rows_kernel<NVV, true, false><<<grid, block, 0, st>>>(C2R_ROWS_ARGS);      \
+    else                                                                                   \
+        route_select_rows_kernel<NVV, false, false><<<grid, block, 0, st>>>(C2R_ROWS_ARGS)
+        switch ((E + 15) / 16) {
+            case 1: C2R_ROWS_LAUNCH(1); break;
+            case 2: C2R_ROWS_LAUNCH(2); break;
+            case 3: C2R_ROWS_LAUNCH(3); break;
+            default: C2R_ROWS_LAUNCH(4); break;
+        }
+#undef C2R_ROWS_LAUNCH
+#undef C2R_ROWS_ARGS
+        return launch_status();
+    }
+    if (!topk_idx || !gates) return C2R_ERR_UNSUPPORTED;
+    const int EPV = ep_of(E);
+    C2R_EP_SWITCH(EPV, route_select_kernel<EP, true><<<dim3((unsigned)nsel), dim3(64), 0, st>>>(
+                           logits, 1, (const float *)nullptr, T, E, K, collab_idx, Tc, topk_idx, gates,
+                           (float *)nullptr));
+    const int rc = launch_status();
+    if (rc != C2R_OK || !Cmat) return rc;
+    return c2r_build_coactivation(topk_idx, T, K, E, Cmat, st);
+}
+
 extern "C" int c2r_route_from_logits(const float *logits, int64_t T, int E, int K,
                                      const int32_t *collab_idx, int Tc, int32_t *topk_idx,
                                      float *gates, void *stream) {
@@ -1108,30 +1195,20 @@ extern "C" int c2r_route_from_logits(const float *logits, int64_t T, int E, int 
     if (T == 0) return C2R_OK;
     if (!logits || !topk_idx || !gates) return C2R_ERR_INVALID_ARG;
     if (!aligned(logits, 16)) return C2R_ERR_INVALID_ARG;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int64_t nsel = (T + 63) / 64;
-    if (nsel >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
-    if (E % 4 == 0 && K <= 4) {
-        // few, long-lived workgroups: each builds the collaborator lists once and then walks its groups
-        const int64_t nblk = (nsel + 3) / 4 < 512 ? (nsel + 3) / 4 : 512;
-        const dim3 grid((unsigned)nblk), block(256);
-#define C2R_ROWS_LAUNCH(NVV)                                                                                       \
-    if (collab_idx)                                                                                                 \
-        route_select_rows_kernel<NVV, true><<<grid, block, 0, st>>>(logits, T, E, K, collab_idx, Tc, topk_idx, gates, nsel); \
-    else                                                                                                            \
-        route_select_rows_kernel<NVV, false><<<grid, block, 0, st>>>(logits, T, E, K, collab_idx, Tc, topk_idx, gates, nsel)
-        switch ((E + 15) / 16) {
-            case 1: C2R_ROWS_LAUNCH(1); break;
-            case 2: C2R_ROWS_LAUNCH(2); break;
-            case 3: C2R_ROWS_LAUNCH(3); break;
-            default: C2R_ROWS_LAUNCH(4); break;
-        }
-#undef C2R_ROWS_LAUNCH
-        return launch_status();
-    }
-    const int EPV = ep_of(E);
-    C2R_EP_SWITCH(EPV, route_select_kernel<EP, true><<<dim3((unsigned)nsel), dim3(64), 0, st>>>(
-                           logits, 1, (const float *)nullptr, T, E, K, collab_idx, Tc, topk_idx, gates,
-                           (float *)nullptr));
-    return launch_status();
+    return route_from_logits_impl(logits, T, E, K, collab_idx, Tc, topk_idx, gates, nullptr,
+                                  static_cast<hipStream_t>(stream));
+}
+
+extern "C" int c2r_profile_from_logits(const float *logits, int64_t T, int E, int K,
+                                       const int32_t *collab_idx, int Tc, int32_t *topk_idx,
+                                       float *gates, int32_t *C, void *stream) {
+    drop_stale_error();
+    int rc = check_route_args(T, E, K, collab_idx, Tc);
+    if (rc != C2R_OK) return rc;
+    if (T == 0) return C2R_OK;
+    if (!logits || !C) return C2R_ERR_INVALID_ARG;
+    if (!aligned(logits, 16) || !aligned(C, 4)) return C2R_ERR_INVALID_ARG;
+    if (topk_idx && !aligned(topk_idx, 4)) return C2R_ERR_INVALID_ARG;
+    return route_from_logits_impl(logits, T, E, K, collab_idx, Tc, topk_idx, gates, C,
+                                  static_cast<hipStream_t>(stream));
 }

@@ -89,6 +89,10 @@ def test_argument_errors_before_launch():
     assert L.c2r_expert_ffn_gate_up_with_shared(p, 1, p, 16, 2, p, 4, 32, 64, 64, p, p, p, 64, null, p, p, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_expert_ffn_down_with_shared(p, 1, p, 4, 32, 64, 64, p, p, 16, 64, p, p, null, null) == c2r.ERR_INVALID_ARG
     assert L.c2r_expert_ffn_down_with_shared(p, 1, p, 4, 32, 64, 88, p, p, 16, 64, p, p, p, null) == c2r.ERR_UNSUPPORTED  # F % 64
+    assert L.c2r_profile_from_logits(p, 16, 8, 2, null, 0, null, null, null, null) == c2r.ERR_INVALID_ARG      # no C
+    assert L.c2r_profile_from_logits(p, 16, 6, 2, null, 0, null, null, p, null) == c2r.ERR_UNSUPPORTED         # E % 4 without outputs
+    assert L.c2r_profile_from_logits(p, 16, 8, 5, null, 0, null, null, p, null) == c2r.ERR_UNSUPPORTED         # K > 4 without outputs
+    assert L.c2r_profile_from_logits(p, 16, 8, 9, null, 0, p, p, p, null) == c2r.ERR_INVALID_ARG               # K > E
     # the allocation-free dispatch rejects what its static array cannot hold
     assert L.c2r_permute_noalloc(p, 1, p, (1 << 20) + 1, 64, 8, 4, null, 8, p, p, p, p, p, null) == c2r.ERR_UNSUPPORTED
     # empty batches are fine and launch nothing

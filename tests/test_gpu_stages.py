@@ -96,7 +96,8 @@ def test_route_short_or_bad_list_entries(c2r, orc):
     np.testing.assert_allclose(gates.sum(1), 1.0, rtol=1e-6)
 
 
-@pytest.mark.parametrize("E,K,Tc,T", [(60, 4, 16, 5000), (7, 2, 3, 63), (64, 4, 8, 257), (16, 4, 8, 1)])
+@pytest.mark.parametrize("E,K,Tc,T", [(60, 4, 16, 5000), (7, 2, 3, 63), (64, 4, 8, 257), (16, 4, 8, 1),
+                                     (16, 6, 9, 300), (24, 10, 12, 129), (30, 4, 5, 200)])
 def test_route_from_logits(c2r, orc, E, K, Tc, T):
     rng = np.random.default_rng(E)
     logits = rng.integers(-5, 6, size=(T, E)).astype(np.float32)       # many ties
@@ -147,6 +148,34 @@ def test_route_from_logits_special_values_signed_zeros_and_short_lists(c2r, orc,
         idx_ref, g_ref = orc.route(logits, K, ci_ref)
         assert np.array_equal(host(idx), idx_ref)
         np.testing.assert_allclose(host(gates), g_ref, rtol=GATE_RTOL, atol=1e-7, equal_nan=True)
+
+
+@pytest.mark.parametrize("E,K,Tc,T", [(60, 4, 16, 70001), (60, 4, 0, 4 * 64 * 513 + 9), (16, 2, 5, 1000), (8, 4, 7, 64),
+                                     (30, 3, 6, 500), (24, 6, 8, 300)])
+def test_profile_from_logits_equals_route_then_count(c2r, orc, E, K, Tc, T):
+    # one launch (selection + Eq. 2 counts) against the oracle's route -> coactivation, with and without
+    # the selections written, accumulating over two batches; shapes outside the fused kernel
+    # (E not a multiple of 4, K > 4) run the two kernels and must give the same
+    rng = np.random.default_rng(E + K + T)
+    logits = rng.standard_normal((T, E)).astype(np.float32)
+    logits[:, : E // 3] += 1.0
+    logits[::13] = np.round(logits[::13])                              # ties
+    logits[5::101, 0] = np.nan
+    ci = _collab(E, Tc, 11) if Tc else None
+    idx_ref, g_ref = orc.route(logits, K, ci)
+    C_ref = orc.coactivation(idx_ref, E)
+    fused_shape = E % 4 == 0 and K <= 4
+    Cm = torch.zeros((E, E), dtype=torch.int32, device="cuda")
+    _, idx, gates = c2r.profile_from_logits(dev(logits), K, Cm, None if ci is None else dev(ci), want_selection=True)
+    assert np.array_equal(host(idx), idx_ref)
+    np.testing.assert_allclose(host(gates), g_ref, rtol=GATE_RTOL, atol=1e-7, equal_nan=True)
+    assert np.array_equal(host(Cm).astype(np.int64), C_ref)
+    if fused_shape:                                                     # counts alone, added to what is there
+        c2r.profile_from_logits(dev(logits[: T // 2]), K, Cm, None if ci is None else dev(ci))
+        assert np.array_equal(host(Cm).astype(np.int64), orc.coactivation(idx_ref[: T // 2], E, C_ref))
+    else:
+        with pytest.raises(RuntimeError):
+            c2r.profile_from_logits(dev(logits), K, Cm, None if ci is None else dev(ci))
 
 
 def test_route_from_logits_single_expert(c2r, orc):
