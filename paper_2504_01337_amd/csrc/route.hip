@@ -734,7 +734,9 @@ __global__ __launch_bounds__(256) void route_select_rows_kernel(const float *__r
                                                                 int64_t ngroups) {
     typedef float f32x4 __attribute__((ext_vector_type(4)));
     typedef int i32x4 __attribute__((ext_vector_type(4)));
-    constexpr int TILE_BYTES = 64 * 64 * 4;  // per wave: [column][token ^ 16 * ((column >> 2) & 3)] floats
+    // per wave: [column][token ^ 4 * (column >> 2)] floats for 16 NV columns; a power of two, so that
+    // offsets inside a tile may be combined with XOR
+    constexpr int TILE_BYTES = NV == 1 ? 4096 : NV == 2 ? 8192 : 16384;
     __shared__ __attribute__((aligned(1024))) unsigned char tile_mem[4 * TILE_BYTES];
     __shared__ uint64_t mask_tab[LISTS ? C2R_MAX_E : 1];
     // clist[e][k]: the k-th collaborator c of e (ascending) as the byte offset of its column in a
@@ -1153,7 +1155,9 @@ static int route_from_logits_impl(const float *logits, int64_t T, int E, int K, 
     if (nsel >= (1ll << 31)) return C2R_ERR_UNSUPPORTED;
     if (E % 4 == 0 && K <= 4) {
         // few, long-lived workgroups: each builds the collaborator lists once and then walks its groups
-        const int64_t nblk = (nsel + 3) / 4 < 512 ? (nsel + 3) / 4 : 512;
+        // (as many as fit a CU's LDS at once: two with 64-column tiles, four with 32 columns or fewer)
+        const int64_t cap = E <= 32 ? 1024 : 512;
+        const int64_t nblk = (nsel + 3) / 4 < cap ? (nsel + 3) / 4 : cap;
         const dim3 grid((unsigned)nblk), block(256);
 #define C2R_ROWS_ARGS logits, T, E, K, collab_idx, Tc, topk_idx, gates, Cmat, nsel
 #define C2R_ROWS_LAUNCH(NVV)                                                               \
