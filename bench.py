@@ -234,6 +234,7 @@ def bench_profiling(args, w, torch, np, c2r, wl):
                 isolated[name][mode + "_us"] = us
                 isolated[name][mode + "_GBps"] = nbytes / us / 1e3
                 isolated[name][mode + "_frac_hbm"] = nbytes / us / 1e3 / PEAK["hbm_GBps"]
+                isolated[name][mode + "_frac_of_copy"] = (nbytes / us / 1e3) / isolated["device_copy_192MB"][mode]["GBps"]
         step()
         torch.cuda.synchronize()
     roofline = {"kernel": dom_kernel + (" (top-K of stored logits and Eq. 2 counts in one launch)" if fused
@@ -668,6 +669,8 @@ def main():
             isolated.setdefault("permute_standalone_with_rows", {})[mode + "_us"] = us
             isolated["permute_standalone_with_rows"][mode + "_GBps"] = perm_bytes / us / 1e3
             isolated["permute_standalone_with_rows"][mode + "_frac_hbm"] = perm_bytes / us / 1e3 / PEAK["hbm_GBps"]
+            isolated["permute_standalone_with_rows"][mode + "_frac_of_copy"] = \
+                (perm_bytes / us / 1e3) / isolated["device_copy_192MB"][mode]["GBps"]
             us_idx = cold.time(lambda: None, lambda: c2r.permute(x, L.idx, L.E, L.local_slot, L.E_local, ws=L.ws_perm,
                                out=(L.counts, L.offsets, L.perm, L.inv_perm, None), rows=False), n_it, mode)
             us_rows = max(us - us_idx, 1e-3)
