@@ -171,6 +171,14 @@ def test_profiling_c4_full_size(c2r, orc):
     assert np.array_equal(host(collab), orc.collaborators(C_ref, w.Tc))
     sel = np.random.default_rng(4).permutation(w.T)[:4096]
     np.testing.assert_allclose(host(gates)[sel], g_ref[sel], rtol=GATE_RTOL, atol=1e-7)
+    # the one-launch form (selection and counts; the selections not written), as bench.py times it,
+    # then once more with the selections written, adding to the same matrix
+    Cf = torch.zeros_like(Cm)
+    c2r.profile_from_logits(lg, w.K, Cf)
+    assert np.array_equal(host(Cf).astype(np.int64), C_ref)
+    _, idx2, gates2 = c2r.profile_from_logits(lg, w.K, Cf, want_selection=True)
+    assert np.array_equal(host(Cf).astype(np.int64), 2 * C_ref)
+    assert torch.equal(idx2, idx) and torch.equal(gates2, gates)
 
 
 def test_layer_forward_in_a_captured_graph(c2r, orc):
