@@ -213,9 +213,11 @@ int c2r_permute_noalloc(const void *x, c2r_dtype dt, const int32_t *topk_idx, in
  * Concurrency (this and every other c2r_expert_ffn_* call, bf16 shapes of the fast kernel): a
  * launch hands its tiles out through a set of counters in a static device array; the library
  * holds 64 sets per GPU and gives them to launches in turn, and a set is all zero again when its
- * launch ends.  Any number of launches may be QUEUED; at most 64 may be RUNNING on one GPU at the
- * same time (on whatever streams).  A launch recorded into a HIP graph keeps the set it was given
- * at capture: replays of that graph must not overlap each other, nor 64 or more other launches.
+ * launch ends.  Two launches that were given the same set (every 64th call) must not RUN at the
+ * same time: on one stream they never do, however many are queued; a caller that spreads these
+ * calls over several streams keeps fewer than 64 of them outstanding (enqueued and not finished)
+ * per GPU.  A launch recorded into a HIP graph keeps the set it was given at capture: replays of
+ * that graph must not overlap each other.
  */
 int c2r_expert_ffn(const void *x_perm, c2r_dtype dt, const int32_t *offsets, int E_local,
                    int64_t A_cap, int d, int F, const void *w_gate, const void *w_up,
