@@ -355,8 +355,12 @@ __device__ __forceinline__ void ffn_tile(const FfnLaunchArgs Lp, unsigned char *
         rdB[j] = (uint32_t)(tiny_tile ? T_A_BYTES : short_tile ? L_A_BYTES : A_BYTES) + (uint32_t)(r + fr) * ROWB;
     }
     const int sw = swz_key(fr);
-    // waves whose whole M range lies past the group's end only help with the copies
-    const bool active = __builtin_amdgcn_readfirstlane(rows - wm * TM) > 0;
+    // waves whose whole M range lies past the group's end, or whose output columns all lie past N (the
+    // last N-tile of a width that is not a multiple of the tile: 688 = 5 x 128 + 48), only help with
+    // the copies: their results would be thrown away, and under the chip's power limit matrix
+    // instructions on padding cost the other waves clock
+    const bool cols_exist = n0 + (MODE == 0 ? wn * (TN / 2) : wn * TN) < N;  // (uniform per wave)
+    const bool active = __builtin_amdgcn_readfirstlane(rows - wm * TM) > 0 && cols_exist;
 
     bf16x8 aset[2][4], bset[2][4];
     // A fragments of k range kq (0, 1) and 64-row half `half` into set `set`
@@ -516,7 +520,7 @@ __device__ __forceinline__ void ffn_tile(const FfnLaunchArgs Lp, unsigned char *
                 wait_copies_but_and_lds<0>();
             lds_barrier();  // every wave's reads of slice kt-1 have returned: its stage is free
             if (kt + 3 < nk) tiny_copy(kt + 3);
-            if (wm == 0) {
+            if (wm == 0 && cols_exist) {
                 const unsigned char *stage = smem + (kt & (T_NSTAGE - 1)) * T_STAGE_BYTES;
 #pragma unroll
                 for (int kq = 0; kq < 2; ++kq) {
@@ -560,7 +564,7 @@ __device__ __forceinline__ void ffn_tile(const FfnLaunchArgs Lp, unsigned char *
                 wait_copies_but_and_lds<0>();
             lds_barrier();
             if (kt + 2 < nk) short_copy(kt + 2);
-            if (wm == 0) {
+            if (wm == 0 && cols_exist) {
                 const unsigned char *stage = smem + (kt % L_NSTAGE) * L_STAGE_BYTES;
 #pragma unroll
                 for (int kq = 0; kq < 2; ++kq) {
