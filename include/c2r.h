@@ -224,8 +224,9 @@ int c2r_expert_ffn(const void *x_perm, c2r_dtype dt, const int32_t *offsets, int
                    const void *w_down, void *y_perm, void *ws, size_t ws_bytes, void *stream);
 
 /*
- * The two passes of c2r_expert_ffn as calls of their own (same arguments and
- * limits), for callers that time them or put other work between them:
+ * The two passes of c2r_expert_ffn (the expert computation of Sec. 3.1, shapes of Sec. 4.1) as
+ * calls of their own (same arguments and limits), for callers that time them or put other work
+ * between them:
  *   gate_up : h[r, f]      = silu(W_gate,e[f,:] . x_perm[r]) * (W_up,e[f,:] . x_perm[r])
  *   down    : y_perm[r, j] = W_down,e[j,:] . h[r]
  * h : [A_cap, F] of dt, caller-owned (what c2r_expert_ffn keeps in its workspace).

@@ -29,6 +29,23 @@ def test_header_symbols_exported():
     assert c2r.route_chunk() == 256
 
 
+def test_every_entry_point_is_documented_with_its_passage():
+    # the comment in front of each declaration cites the passage of the paper that defines the operation
+    # (a section, an equation or a table) - or, for the calls no passage defines, says what they are for
+    with open(os.path.join(ROOT, "include", "c2r.h")) as f:
+        text = f.read()
+    no_passage = {"c2r_version": "version", "c2r_route_chunk": "order", "c2r_workspace_bytes": "scratch",
+                  "c2r_permute_noalloc": "cannot allocate"}
+    for m in re.finditer(r"/\*(.*?)\*/\s*(?:int|size_t)\s+(c2r_[a-z0-9_]+)\s*\(", text, flags=re.S):
+        comment, name = m.group(1), m.group(2)
+        comment = comment.split("/*")[-1]
+        if name in no_passage:
+            assert no_passage[name] in comment, name
+        else:
+            assert re.search(r"Sec\. \d|Eq\. \d|Table \d", comment), name
+        assert len(comment.strip()) > (40 if name in no_passage else 80), name
+
+
 def test_workspace_query_is_host_only():
     c2r = _lib()
     assert c2r.workspace_bytes(c2r.STAGE_COACTIVATION, 1000, 64, 8, 2, 0, c2r.F32) == 0
